@@ -1,0 +1,163 @@
+"""ctypes/numpy front end of the CPU oracle (TEST INFRASTRUCTURE, not product code).
+
+Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It never imports the HIP package.
+All arithmetic lives in ``kvq_oracle.c``; this file only marshals numpy arrays
+and chains the C calls (quantize -> dequantize -> attention) per head.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kvq_oracle.c")
+_LIB = os.path.join(_HERE, "libkvq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile kvq_oracle.c with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
+               "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    dp = ctypes.POINTER(ctypes.c_double)
+    fp = ctypes.POINTER(ctypes.c_float)
+    bp = ctypes.POINTER(ctypes.c_uint8)
+    i64, ci, cd = ctypes.c_int64, ctypes.c_int, ctypes.c_double
+    lib.kvqo_num_threads.restype = ci
+    lib.kvqo_hadamard.argtypes = [ci, dp, dp]
+    lib.kvqo_quantize_rows.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp]
+    lib.kvqo_dequantize_rows.argtypes = [i64, ci, ci, bp, fp, fp, dp]
+    lib.kvqo_log_sinhc.argtypes = [cd]
+    lib.kvqo_log_sinhc.restype = cd
+    lib.kvqo_correction.argtypes = [ci, ci, dp, dp, cd, ci]
+    lib.kvqo_correction.restype = cd
+    lib.kvqo_attention.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, dp, dp]
+    _lib = lib
+    return lib
+
+
+def _d(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _p(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def num_threads() -> int:
+    return int(_load().kvqo_num_threads())
+
+
+def hadamard(x) -> np.ndarray:
+    """Unnormalised H_d x for one vector."""
+    x = _d(x)
+    u = np.empty_like(x)
+    if _load().kvqo_hadamard(x.shape[0], _p(x, ctypes.c_double), _p(u, ctypes.c_double)):
+        raise ValueError("hadamard: size must be a power of two")
+    return u
+
+
+def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True
+             ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """x [rows][d] -> codes uint8 [rows][d], scale float32 [rows][G], zero float32 [rows][G]."""
+    x = _d(x)
+    rows, d = x.shape
+    group = d if group is None else group
+    codes = np.empty((rows, d), dtype=np.uint8)
+    scale = np.empty((rows, d // group), dtype=np.float32)
+    zero = np.empty((rows, d // group), dtype=np.float32)
+    rc = _load().kvqo_quantize_rows(rows, d, bits, group, int(rotate), _p(x, ctypes.c_double),
+                                    _p(codes, ctypes.c_uint8), _p(scale, ctypes.c_float),
+                                    _p(zero, ctypes.c_float))
+    if rc:
+        raise ValueError("quantize: bad arguments")
+    return codes, scale, zero
+
+
+def dequantize(codes, scale, zero) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scale = np.ascontiguousarray(scale, dtype=np.float32)
+    zero = np.ascontiguousarray(zero, dtype=np.float32)
+    rows, d = codes.shape
+    group = d // scale.shape[1]
+    out = np.empty((rows, d), dtype=np.float64)
+    if _load().kvqo_dequantize_rows(rows, d, group, _p(codes, ctypes.c_uint8), _p(scale, ctypes.c_float),
+                                    _p(zero, ctypes.c_float), _p(out, ctypes.c_double)):
+        raise ValueError("dequantize: bad arguments")
+    return out
+
+
+def log_sinhc(a: float) -> float:
+    return float(_load().kvqo_log_sinhc(float(a)))
+
+
+def correction(qv, step, sigma: float, mode: int) -> float:
+    """b for one (query, key): qv [d] in the key's basis, step [G]; mode 0 off, 1 Taylor, 2 exact."""
+    qv, step = _d(qv), _d(np.atleast_1d(step))
+    d = qv.shape[0]
+    return float(_load().kvqo_correction(d, d // step.shape[0], _p(qv, ctypes.c_double),
+                                         _p(step, ctypes.c_double), float(sigma), int(mode)))
+
+
+def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, correction: int = 1,
+              rotate: bool = True) -> Tuple[np.ndarray, np.ndarray]:
+    """One head.  q [m][d]; khat, vhat [ns][d]; kstep [ns][G]; kr, vr [nr][d] -> (out [m][d], P_S [m])."""
+    q = _d(q)
+    m, d = q.shape
+    khat = _d(khat).reshape(-1, d)
+    vhat = _d(vhat).reshape(-1, d)
+    kr = _d(kr).reshape(-1, d)
+    vr = _d(vr).reshape(-1, d)
+    ns, nr = khat.shape[0], kr.shape[0]
+    kstep = _d(kstep).reshape(ns, -1) if ns else np.zeros((0, 1))
+    G = kstep.shape[1] if ns else 1
+    sigma = 1.0 / np.sqrt(d) if sigma is None else float(sigma)
+    out = np.empty((m, d), dtype=np.float64)
+    mass = np.empty((m,), dtype=np.float64)
+    rc = _load().kvqo_attention(d, d // G, m, ns, nr, _p(q, ctypes.c_double), _p(khat, ctypes.c_double),
+                                _p(kstep, ctypes.c_double), _p(vhat, ctypes.c_double),
+                                _p(kr, ctypes.c_double), _p(vr, ctypes.c_double), sigma,
+                                int(correction), int(rotate), _p(out, ctypes.c_double),
+                                _p(mass, ctypes.c_double))
+    if rc:
+        raise ValueError("attention: bad arguments")
+    return out, mass
+
+
+def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
+                    sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True):
+    """Whole path for [token][head][d] inputs: quantize the cached K/V per head, then attention.
+
+    Returns (out [m][heads][d], P_S [heads][m], quantized) where quantized holds the
+    per-head codes / scales / zeros of K and V for parity checks.
+    """
+    q = np.asarray(q)
+    m, heads, d = q.shape
+    out = np.empty((m, heads, d), dtype=np.float64)
+    mass = np.empty((heads, m), dtype=np.float64)
+    quantized = []
+    for h in range(heads):
+        kc, ks, kz = quantize(np.asarray(k_cached)[:, h, :], bits, group, rotate)
+        vc, vs, vz = quantize(np.asarray(v_cached)[:, h, :], bits, group, rotate)
+        o, p = attention(q[:, h, :], dequantize(kc, ks, kz), ks, dequantize(vc, vs, vz),
+                         np.asarray(k_cur)[:, h, :], np.asarray(v_cur)[:, h, :], sigma, correction, rotate)
+        out[:, h, :] = o
+        mass[h] = p
+        quantized.append(dict(k_codes=kc, k_scale=ks, k_zero=kz, v_codes=vc, v_scale=vs, v_zero=vz))
+    return out, mass, quantized

@@ -1,0 +1,283 @@
+/*
+ * kvq_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * A plain, slow, double-precision CPU statement of what the quantized-KV chunk
+ * attention path computes, written from the paper.  Only tests, the smoke check
+ * and the benchmark's cpu_baseline leg may call it.  It shares no code, header,
+ * table or constant generator with the HIP library.
+ *
+ * Every function is the definition written out: dense +-1 sums for the
+ * Hadamard rotation, the literal round-to-nearest quantizer, a full score row
+ * per query followed by one softmax over [cached | current] keys.  No blocking,
+ * no online softmax, no fast transform.  OpenMP is used only to run independent
+ * rows on several cores.
+ *
+ * Pins (tests/test_oracle_*.py): closed forms for the exponential moment of
+ * uniform noise, Monte-Carlo on the scalar case, orthogonality of the rotation,
+ * the |error| <= step/2 bound, hand-worked rows, textbook softmax attention via
+ * an independent numpy formula, permutation invariance, and special cases
+ * (step 0, no cache, per-channel steps).  The paper prints no worked numeric
+ * example, so nothing here is pinned to printed numbers.
+ *
+ * Build: gcc -O2 -std=c99 -fopenmp -ffp-contract=off -shared -fPIC
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Entry (r, c) of the Sylvester Hadamard matrix of any power-of-two order:
+ * +1 when r and c share an even number of set bits, else -1. */
+static double hadamard_sign(unsigned r, unsigned c)
+{
+    unsigned x = r & c, parity = 0;
+    while (x) { parity ^= (x & 1u); x >>= 1; }
+    return parity ? -1.0 : 1.0;
+}
+
+static int is_pow2(int d) { return d > 0 && (d & (d - 1)) == 0; }
+
+/* 1/sqrt(d) rounded once to double; written out for the two supported sizes so
+ * the value does not depend on a library sqrt. */
+static double inv_sqrt_d(int d)
+{
+    if (d == 64) return 0.125;
+    if (d == 128) return 0.08838834764831845; /* sqrt(2)/16 */
+    return 1.0 / sqrt((double)d);
+}
+
+int kvqo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* u = H_d x, the unnormalised rotation (Preliminaries, "Hadamard rotation").
+ * Each output is one left-to-right sum of +-x_c. */
+int kvqo_hadamard(int d, const double *x, double *u)
+{
+    if (!is_pow2(d)) return 1;
+    for (int r = 0; r < d; ++r) {
+        double s = 0.0;
+        for (int c = 0; c < d; ++c) s += hadamard_sign((unsigned)r, (unsigned)c) * x[c];
+        u[r] = s;
+    }
+    return 0;
+}
+
+/*
+ * Asymmetric round-to-nearest quantization of `rows` vectors (Eq. 1 and the
+ * sentence after it: scale and zero-point cover the [min, max] range), per
+ * group of `group` consecutive channels, after an optional Hadamard rotation.
+ *
+ *   u      = H_d x                      (rotate != 0; otherwise u = x)
+ *   lo, hi = min, max of u over the group; a constant group has its range
+ *            widened to include 0 (all-zero group: step 0, codes 0)
+ *   inv    = L / (hi - lo),  L = 2^bits - 1
+ *   z      = -rint(lo * inv)            (integer, any sign)
+ *   code   = clamp(rint(u * inv) + z, 0, L)
+ *   scale  = float((hi - lo) / L * n)   n = 1/sqrt(d) with rotation, 1 without
+ *   zero   = float(z)
+ * so that (code - zero) * scale reconstructs the normalised rotated vector.
+ * rint rounds ties to even.  Decisions are taken on the unnormalised u; the
+ * positive factor n only enters the stored scale.
+ *
+ * x: [rows][d] doubles.  codes: [rows][d] bytes.  scale, zero: [rows][d/group].
+ */
+int kvqo_quantize_rows(int64_t rows, int d, int bits, int group, int rotate,
+                       const double *x, uint8_t *codes, float *scale, float *zero)
+{
+    if (rows < 0 || d <= 0 || group <= 0 || d % group != 0) return 1;
+    if (bits < 1 || bits > 8) return 1;
+    if (rotate && !is_pow2(d)) return 1;
+    const double L = (double)((1 << bits) - 1);
+    const double norm = rotate ? inv_sqrt_d(d) : 1.0;
+    const int G = d / group;
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < rows; ++t) {
+        double *u = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!u) { failed = 1; continue; }
+        const double *xr = x + t * d;
+        if (rotate) kvqo_hadamard(d, xr, u);
+        else memcpy(u, xr, sizeof(double) * (size_t)d);
+        for (int j = 0; j < G; ++j) {
+            const double *ug = u + j * group;
+            uint8_t *cg = codes + t * d + j * group;
+            double lo = ug[0], hi = ug[0];
+            for (int c = 1; c < group; ++c) {
+                if (ug[c] < lo) lo = ug[c];
+                if (ug[c] > hi) hi = ug[c];
+            }
+            if (hi == lo) {
+                if (lo > 0.0) lo = 0.0;
+                if (hi < 0.0) hi = 0.0;
+            }
+            if (hi == lo) {
+                for (int c = 0; c < group; ++c) cg[c] = 0;
+                scale[t * G + j] = 0.0f;
+                zero[t * G + j] = 0.0f;
+                continue;
+            }
+            const double range = hi - lo;
+            const double inv = L / range;
+            const double step = range / L;
+            const double z = -rint(lo * inv);
+            for (int c = 0; c < group; ++c) {
+                double k = rint(ug[c] * inv) + z;
+                if (k < 0.0) k = 0.0;
+                if (k > L) k = L;
+                cg[c] = (uint8_t)k;
+            }
+            scale[t * G + j] = (float)(step * norm);
+            zero[t * G + j] = (float)z;
+        }
+        free(u);
+    }
+    return failed;
+}
+
+/* Reconstruction x^ = (x_q - z) * step (sentence after Eq. 1), in the basis the
+ * codes were taken in.  out: [rows][d] doubles. */
+int kvqo_dequantize_rows(int64_t rows, int d, int group, const uint8_t *codes,
+                         const float *scale, const float *zero, double *out)
+{
+    if (rows < 0 || d <= 0 || group <= 0 || d % group != 0) return 1;
+    const int G = d / group;
+    for (int64_t t = 0; t < rows; ++t)
+        for (int c = 0; c < d; ++c) {
+            const int64_t g = t * G + c / group;
+            out[t * d + c] = ((double)codes[t * d + c] - (double)zero[g]) * (double)scale[g];
+        }
+    return 0;
+}
+
+/* log(sinh(a)/a), the per-channel log moment of uniform noise (Eq. 12), in a
+ * form that neither overflows for large |a| nor cancels for small |a|. */
+double kvqo_log_sinhc(double a)
+{
+    a = fabs(a);
+    if (a < 1e-3) {
+        const double a2 = a * a;
+        return a2 / 6.0 - a2 * a2 / 180.0 + a2 * a2 * a2 / 2835.0;
+    }
+    /* sinh(a)/a = e^a (1 - e^{-2a}) / (2a) */
+    return a + log1p(-exp(-2.0 * a)) - log(2.0 * a);
+}
+
+/*
+ * Correction b for one (query, key) pair.
+ *   qv    : the query in the basis the key was quantized in (rotated query
+ *           under rotation; Appendix "Extension to QuaRot"), d values
+ *   step  : the key's step size per group, G = d/group values
+ *   sigma : softmax scale (1/sqrt(d) in the paper)
+ *   mode 1: second-order Taylor form  sigma^2/24 * sum_j step_j^2 * ||qv_j||^2
+ *           (Eq. 13 / Eq. 15; sigma^2 = 1/d gives the paper's 1/(24 d))
+ *   mode 2: exact form  sum_c log(sinh(a_c)/a_c),  a_c = sigma*qv_c*step/2 (Eq. 12)
+ *   mode 0: 0
+ */
+double kvqo_correction(int d, int group, const double *qv, const double *step,
+                       double sigma, int mode)
+{
+    if (mode == 0) return 0.0;
+    const int G = d / group;
+    double b = 0.0;
+    if (mode == 1) {
+        for (int j = 0; j < G; ++j) {
+            double nu = 0.0;
+            for (int c = j * group; c < (j + 1) * group; ++c) nu += qv[c] * qv[c];
+            b += step[j] * step[j] * nu;
+        }
+        return b * sigma * sigma / 24.0;
+    }
+    for (int c = 0; c < d; ++c) b += kvqo_log_sinhc(0.5 * sigma * qv[c] * step[c / group]);
+    return b;
+}
+
+/*
+ * Chunk attention for one head (Alg. 1 with Eq. 2-4), every step in order:
+ *
+ *   qv        = Hn q          (rotate != 0; Hn = H_d / sqrt(d))   else qv = q
+ *   s^_i      = sigma * qv . k^_i          i in S  (cached, dequantized keys)
+ *   s_j       = sigma * q  . k_j           j in R  (current keys)
+ *   b_i       = correction(qv, step_i)     subtracted from cached scores only
+ *   p         = softmax(concat(s^ - b, s)) with the row maximum subtracted
+ *   P_S       = sum_{i in S} p_i
+ *   o         = Hn^T (sum_{i in S} p_i v^_i) + sum_{j in R} p_j v_j
+ *
+ * k^, v^ [ns][d]: dequantized cached keys / values in the basis they were
+ * quantized in (rotated and normalised when rotate != 0).  kstep [ns][d/group]:
+ * the stored step of each cached key group.  Current keys / values kr, vr
+ * [nr][d] and queries q [m][d] are in the original basis, as is out [m][d].
+ * mass_cached [m] (nullable) receives P_S.  ns == 0 or nr == 0 are allowed,
+ * not both.
+ */
+int kvqo_attention(int d, int group, int64_t m, int64_t ns, int64_t nr,
+                   const double *q, const double *khat, const double *kstep,
+                   const double *vhat, const double *kr, const double *vr,
+                   double sigma, int correction, int rotate,
+                   double *out, double *mass_cached)
+{
+    if (d <= 0 || group <= 0 || d % group != 0 || m < 0 || ns < 0 || nr < 0) return 1;
+    if (ns + nr == 0) return 1;
+    if (rotate && !is_pow2(d)) return 1;
+    if (correction < 0 || correction > 2) return 1;
+    const int G = d / group;
+    const double norm = inv_sqrt_d(d);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < m; ++r) {
+        double *qv = (double *)malloc(sizeof(double) * (size_t)d * 3);
+        double *s = (double *)malloc(sizeof(double) * (size_t)(ns + nr));
+        if (!qv || !s) { failed = 1; free(qv); free(s); continue; }
+        double *acc = qv + d, *tmp = acc + d;
+        const double *qr = q + r * d;
+        if (rotate) {
+            kvqo_hadamard(d, qr, qv);
+            for (int c = 0; c < d; ++c) qv[c] *= norm;
+        } else {
+            memcpy(qv, qr, sizeof(double) * (size_t)d);
+        }
+        for (int64_t i = 0; i < ns; ++i) {
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += qv[c] * khat[i * d + c];
+            s[i] = sigma * dot - kvqo_correction(d, group, qv, kstep + i * G, sigma, correction);
+        }
+        for (int64_t j = 0; j < nr; ++j) {
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += qr[c] * kr[j * d + c];
+            s[ns + j] = sigma * dot;
+        }
+        double top = s[0];
+        for (int64_t i = 1; i < ns + nr; ++i) if (s[i] > top) top = s[i];
+        double zs = 0.0, zr = 0.0;
+        for (int64_t i = 0; i < ns; ++i) { s[i] = exp(s[i] - top); zs += s[i]; }
+        for (int64_t j = ns; j < ns + nr; ++j) { s[j] = exp(s[j] - top); zr += s[j]; }
+        const double z = zs + zr;
+        for (int c = 0; c < d; ++c) acc[c] = 0.0;
+        for (int64_t i = 0; i < ns; ++i) {
+            const double p = s[i] / z;
+            for (int c = 0; c < d; ++c) acc[c] += p * vhat[i * d + c];
+        }
+        if (rotate) {
+            /* Hn is symmetric, so Hn^T acc is the same dense product. */
+            kvqo_hadamard(d, acc, tmp);
+            for (int c = 0; c < d; ++c) acc[c] = tmp[c] * norm;
+        }
+        for (int64_t j = 0; j < nr; ++j) {
+            const double p = s[ns + j] / z;
+            for (int c = 0; c < d; ++c) acc[c] += p * vr[j * d + c];
+        }
+        for (int c = 0; c < d; ++c) out[r * d + c] = acc[c];
+        if (mass_cached) mass_cached[r] = zs / z;
+        free(qv);
+        free(s);
+    }
+    return failed;
+}

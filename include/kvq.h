@@ -1,0 +1,153 @@
+/*
+ * kvq.h -- C ABI of the quantized-KV chunk-attention library for AMD MI355X (gfx950).
+ *
+ * The library implements one hot path of "Quantized Keys Steal Attention: Bias
+ * Correction for KV-Cache Compression in Video Diffusion":
+ *
+ *   kvq_quantize_append   rotate (Hadamard), quantize (asymmetric round-to-nearest,
+ *                         per token) and bit-pack one chunk's keys and values into
+ *                         the cache                      [Preliminaries: Eq. 1,
+ *                         "Quantization granularity", "Hadamard rotation"]
+ *   kvq_chunk_attention   current-chunk queries attend to the packed cache of earlier
+ *                         chunks and to the unquantized keys/values of the current
+ *                         chunk in one joint softmax, with the second-order Taylor
+ *                         correction b subtracted from every cached-key score
+ *                         [Alg. 1; Eq. 2-4, Eq. 13, Eq. 15; App. "Extension to QuaRot"]
+ *
+ * Conventions
+ *   - Plain C types only.  Pointers named dev_* / q / k / v / out / mass_cached are
+ *     DEVICE pointers; everything else is host memory.
+ *   - The caller owns every device buffer, including the cache storage; the library
+ *     never allocates or frees device memory.
+ *   - Launching calls are asynchronous on the HIP stream passed as `hip_stream`
+ *     (a hipStream_t cast to void*; NULL is the default stream).  They return after
+ *     argument validation and enqueue.  Calls that touch the same cache must be
+ *     stream-ordered by the caller.
+ *   - Errors are returned as kvq_status; nothing aborts or throws.  On any error
+ *     nothing has been enqueued and the cache is unchanged.
+ *   - Tensors are [token][head][channel] with element strides `stride_token`,
+ *     `stride_head` (channel stride 1), in the cache's io_dtype.
+ *   - The packed layout inside the cache storage is private to the library; the
+ *     canonical view (one code per byte, scale, zero-point) is available through
+ *     kvq_cache_export.
+ */
+#ifndef KVQ_H
+#define KVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kvq_cache kvq_cache; /* opaque host object */
+
+typedef enum {
+    KVQ_OK = 0,
+    KVQ_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned buffer, bad range */
+    KVQ_ERR_UNSUPPORTED = 2, /* head_dim not 64/128, bits not 2/4, group_size != head_dim, rotate != 1 */
+    KVQ_ERR_CAPACITY = 3,    /* append would exceed capacity_tokens */
+    KVQ_ERR_HIP = 4          /* the HIP runtime refused a launch */
+} kvq_status;
+
+typedef enum { KVQ_BF16 = 0, KVQ_FP32 = 1 } kvq_dtype;
+
+typedef struct {
+    int32_t num_heads;       /* >= 1 */
+    int32_t head_dim;        /* 64 or 128 */
+    int32_t bits;            /* 2 or 4 */
+    int32_t group_size;      /* channels sharing one (scale, zero-point); must equal head_dim (per token) */
+    int32_t rotate;          /* must be 1: normalised Sylvester-Hadamard rotation before quantization */
+    int32_t io_dtype;        /* kvq_dtype of q/k/v/out.  KVQ_BF16 with head_dim 128 runs on the matrix
+                                cores; KVQ_FP32 (and head_dim 64) runs an fp32 vector kernel */
+    int64_t capacity_tokens; /* >= 1; storage is sized for this many tokens per head */
+} kvq_cache_desc;
+
+/* Device bytes the caller must provide for a cache of this description:
+ * 2 * num_heads * cap32 * (head_dim*bits/8 + 8) with cap32 = capacity rounded up to 32 tokens
+ * (codes plus one float scale and one float zero-point per token, for K and for V).
+ * Returns 0 for an invalid or unsupported description. */
+size_t kvq_cache_bytes(const kvq_cache_desc *desc);
+
+/* Creates the host object over caller-provided device storage (`dev_mem`, at least
+ * kvq_cache_bytes(desc) bytes, 256-byte aligned).  The storage need not be initialised.
+ * The cache starts empty. */
+kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t bytes, kvq_cache **out);
+
+/* Frees the host object only; the device storage stays with the caller. */
+void kvq_cache_destroy(kvq_cache *cache);
+
+/* Number of tokens appended so far (host-side counter; -1 for a null cache). */
+int64_t kvq_cache_len(const kvq_cache *cache);
+
+/* Forget every token / every token from new_len on (host-side counter only; 0 <= new_len <= len). */
+kvq_status kvq_cache_reset(kvq_cache *cache);
+kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len);
+
+/*
+ * Append one chunk: for each (token, head) the key and the value vector are rotated by the
+ * normalised Hadamard matrix, quantized to `bits` with one (scale, zero-point) per token
+ *     step = (max - min) / (2^bits - 1),  z = -round(min/step),
+ *     code = clamp(round(x/step) + z, 0, 2^bits - 1)            (round: nearest, ties to even)
+ * and packed.  A constant vector has its range widened to include 0; an all-zero vector gets
+ * step 0.  The rotation is carried out exactly in double precision, so for inputs whose
+ * nonzero magnitudes in one vector span at most 2^38 (BF16 values) the codes, scales and
+ * zero-points are a bit-exact function of the input.
+ *
+ * k, v: device, [n_tokens][num_heads][head_dim] in io_dtype with the given element strides.
+ * n_tokens == 0 is a no-op.  KVQ_ERR_CAPACITY if len + n_tokens > capacity (nothing written).
+ */
+kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                               int64_t stride_token, int64_t stride_head, void *hip_stream);
+
+/*
+ * Corrected chunk attention.  For every head and query row m:
+ *     cached key i in [cache_start, cache_start + cache_len):
+ *         s_i = softmax_scale * (Hn q_m) . k^_i  -  b_mi,
+ *         b_mi = correction ? softmax_scale^2 * step_i^2 * ||q_m||^2 / 24 : 0
+ *     current key j in [0, n_cur):   s_j = softmax_scale * q_m . k_cur_j
+ *     p = softmax over all of them;  out_m = sum_i p_i v^_i (rotated back) + sum_j p_j v_cur_j
+ *     mass_cached[head][m] = sum over cached keys of p      (attention mass P_S; P_R = 1 - P_S)
+ * k^, v^ are the dequantized cache entries, step_i the stored key scale.  With
+ * softmax_scale = 1/sqrt(head_dim) b is the paper's step^2 ||q||^2 / (24 d).
+ *
+ * q, out: device [m][num_heads][head_dim]; k_cur, v_cur: device [n_cur][num_heads][head_dim];
+ * all in io_dtype with the same strides.  mass_cached: device float [num_heads][m] or NULL.
+ * softmax_scale == 0 selects 1/sqrt(head_dim).  correction: 0 off, 1 Taylor.
+ * cache_len == 0 (first chunk) and n_cur == 0 are allowed, not both; m == 0 is a no-op.
+ * `out` must not alias the inputs.
+ */
+kvq_status kvq_chunk_attention(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                               const void *q, const void *k_cur, const void *v_cur,
+                               int64_t m, int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                               float softmax_scale, int correction,
+                               void *out, float *mass_cached, void *hip_stream);
+
+/* Same contract as kvq_chunk_attention, but always runs the fp32 vector-ALU kernel (Alg. 1 in
+ * single precision, no matrix cores): slow, for reference-precision results on any cache. */
+kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                    const void *q, const void *k_cur, const void *v_cur,
+                                    int64_t m, int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                    float softmax_scale, int correction,
+                                    void *out, float *mass_cached, void *hip_stream);
+
+/*
+ * Canonical view of cached tokens [start, start + count), for parity checks and dump/restore.
+ * which: 0 = keys, 1 = values.  codes: device uint8 [num_heads][count][head_dim], one code per
+ * byte, channel order of the rotated vector.  scales, zeros: device float [num_heads][count].
+ * Any of the three output pointers may be NULL.
+ */
+kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count,
+                            uint8_t *codes, float *scales, float *zeros, void *hip_stream);
+
+/* Static, never-null description of a status value. */
+const char *kvq_status_string(kvq_status status);
+
+/* Library version, "major.minor". */
+const char *kvq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVQ_H */

@@ -1,0 +1,213 @@
+// Host layer of the C ABI: argument validation, the cache object, dispatch to the kernels.
+// No device memory is allocated here; the cache storage is carved out of the caller's buffer.
+#include <new>
+
+#include "kvq_internal.h"
+
+struct kvq_cache {
+    kvq_cache_desc desc;
+    kvq::CacheView view;
+    int64_t cap32;  // capacity rounded up to whole tiles
+    int64_t len;    // tokens appended so far
+};
+
+namespace {
+
+kvq_status check_desc(const kvq_cache_desc *d)
+{
+    if (!d) return KVQ_ERR_INVALID_ARG;
+    if (d->num_heads < 1 || d->capacity_tokens < 1 || d->head_dim < 1 || d->bits < 1) return KVQ_ERR_INVALID_ARG;
+    if (d->io_dtype != KVQ_BF16 && d->io_dtype != KVQ_FP32) return KVQ_ERR_INVALID_ARG;
+    if (d->head_dim != 64 && d->head_dim != 128) return KVQ_ERR_UNSUPPORTED;
+    if (d->bits != 2 && d->bits != 4) return KVQ_ERR_UNSUPPORTED;
+    if (d->group_size != d->head_dim) return KVQ_ERR_UNSUPPORTED;
+    if (d->rotate != 1) return KVQ_ERR_UNSUPPORTED;
+    if (d->capacity_tokens > ((int64_t)1 << 40)) return KVQ_ERR_INVALID_ARG;
+    return KVQ_OK;
+}
+
+int64_t round_up_tile(int64_t n) { return (n + kvq::kTileTokens - 1) / kvq::kTileTokens * kvq::kTileTokens; }
+
+size_t elt_bytes(int io_dtype) { return io_dtype == KVQ_BF16 ? 2 : 4; }
+
+// Tensor arguments: 16-byte aligned base, strides that keep every (token, head) vector 16-byte aligned.
+bool tensor_ok(const void *p, int64_t stride_token, int64_t stride_head, int head_dim, int io_dtype)
+{
+    if (!p) return false;
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return false;
+    const int64_t quantum = 16 / (int64_t)elt_bytes(io_dtype);
+    if (stride_token < head_dim || stride_head < head_dim) return false;
+    if (stride_token % quantum != 0 || stride_head % quantum != 0) return false;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t kvq_cache_bytes(const kvq_cache_desc *desc)
+{
+    if (check_desc(desc) != KVQ_OK) return 0;
+    const int64_t cap32 = round_up_tile(desc->capacity_tokens);
+    const int64_t per_token = desc->head_dim * desc->bits / 8 + 8;
+    return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token);
+}
+
+kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t bytes, kvq_cache **out)
+{
+    if (!out) return KVQ_ERR_INVALID_ARG;
+    *out = nullptr;
+    const kvq_status st = check_desc(desc);
+    if (st != KVQ_OK) return st;
+    if (!dev_mem || reinterpret_cast<uintptr_t>(dev_mem) % 256 != 0) return KVQ_ERR_INVALID_ARG;
+    if (bytes < kvq_cache_bytes(desc)) return KVQ_ERR_INVALID_ARG;
+    kvq_cache *c = new (std::nothrow) kvq_cache;
+    if (!c) return KVQ_ERR_INVALID_ARG;
+    c->desc = *desc;
+    c->cap32 = round_up_tile(desc->capacity_tokens);
+    c->len = 0;
+    const int64_t H = desc->num_heads;
+    const int64_t code_bytes = H * c->cap32 * desc->head_dim * desc->bits / 8;  // multiple of 256
+    const int64_t meta_bytes = H * c->cap32 * 4;                                // multiple of 128
+    char *p = static_cast<char *>(dev_mem);
+    kvq::CacheView &v = c->view;
+    v.k_codes = reinterpret_cast<uint32_t *>(p); p += code_bytes;
+    v.v_codes = reinterpret_cast<uint32_t *>(p); p += code_bytes;
+    v.k_scale = reinterpret_cast<float *>(p); p += meta_bytes;
+    v.k_negzero = reinterpret_cast<float *>(p); p += meta_bytes;
+    v.v_scale = reinterpret_cast<float *>(p); p += meta_bytes;
+    v.v_zero_off = reinterpret_cast<float *>(p);
+    v.cap_tiles = c->cap32 / kvq::kTileTokens;
+    v.num_heads = desc->num_heads;
+    v.head_dim = desc->head_dim;
+    v.bits = desc->bits;
+    v.io_dtype = desc->io_dtype;
+    *out = c;
+    return KVQ_OK;
+}
+
+void kvq_cache_destroy(kvq_cache *cache) { delete cache; }
+
+int64_t kvq_cache_len(const kvq_cache *cache) { return cache ? cache->len : -1; }
+
+kvq_status kvq_cache_reset(kvq_cache *cache)
+{
+    if (!cache) return KVQ_ERR_INVALID_ARG;
+    cache->len = 0;
+    return KVQ_OK;
+}
+
+kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len)
+{
+    if (!cache || new_len < 0 || new_len > cache->len) return KVQ_ERR_INVALID_ARG;
+    cache->len = new_len;
+    return KVQ_OK;
+}
+
+kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                               int64_t stride_token, int64_t stride_head, void *hip_stream)
+{
+    if (!cache || n_tokens < 0) return KVQ_ERR_INVALID_ARG;
+    if (n_tokens == 0) return KVQ_OK;
+    const kvq_cache_desc &d = cache->desc;
+    if (!tensor_ok(k, stride_token, stride_head, d.head_dim, d.io_dtype) ||
+        !tensor_ok(v, stride_token, stride_head, d.head_dim, d.io_dtype))
+        return KVQ_ERR_INVALID_ARG;
+    if (n_tokens > d.capacity_tokens - cache->len) return KVQ_ERR_CAPACITY;
+    const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->len, n_tokens, stride_token,
+                                                     stride_head, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return KVQ_ERR_HIP;
+    cache->len += n_tokens;
+    return KVQ_OK;
+}
+
+static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                   const void *q, const void *k_cur, const void *v_cur, int64_t m,
+                                   int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                   float softmax_scale, int correction, void *out, float *mass_cached,
+                                   void *hip_stream, bool force_vector)
+{
+    if (!cache || m < 0 || n_cur < 0 || cache_len < 0 || cache_start < 0) return KVQ_ERR_INVALID_ARG;
+    if (cache_start + cache_len > cache->len) return KVQ_ERR_INVALID_ARG;
+    if (cache_len == 0 && n_cur == 0) return KVQ_ERR_INVALID_ARG;
+    if (correction != 0 && correction != 1) return KVQ_ERR_INVALID_ARG;
+    if (!(softmax_scale >= 0.0f) || !(softmax_scale < 3.0e38f)) return KVQ_ERR_INVALID_ARG;
+    if (m == 0) return KVQ_OK;
+    const kvq_cache_desc &d = cache->desc;
+    if (!tensor_ok(q, stride_token, stride_head, d.head_dim, d.io_dtype) ||
+        !tensor_ok(out, stride_token, stride_head, d.head_dim, d.io_dtype))
+        return KVQ_ERR_INVALID_ARG;
+    if (n_cur > 0 && (!tensor_ok(k_cur, stride_token, stride_head, d.head_dim, d.io_dtype) ||
+                      !tensor_ok(v_cur, stride_token, stride_head, d.head_dim, d.io_dtype)))
+        return KVQ_ERR_INVALID_ARG;
+    if (mass_cached && reinterpret_cast<uintptr_t>(mass_cached) % 4 != 0) return KVQ_ERR_INVALID_ARG;
+    if (out == q || out == k_cur || out == v_cur) return KVQ_ERR_INVALID_ARG;
+    if (m > ((int64_t)1 << 31) - 256 || n_cur > ((int64_t)1 << 31) - 256) return KVQ_ERR_INVALID_ARG;
+
+    kvq::AttentionArgs a;
+    a.cv = cache->view;
+    a.cache_start = cache_start;
+    a.cache_len = cache_len;
+    a.q = q;
+    a.k_cur = k_cur;
+    a.v_cur = v_cur;
+    a.m = m;
+    a.n_cur = n_cur;
+    a.stride_token = stride_token;
+    a.stride_head = stride_head;
+    a.softmax_scale = softmax_scale > 0.0f ? softmax_scale : (d.head_dim == 64 ? 0.125f : 0.088388347648318f);
+    a.correction = correction;
+    a.out = out;
+    a.mass_cached = mass_cached;
+    const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128;
+    const hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = matrix_path ? kvq::launch_attention_mfma(a, s) : kvq::launch_attention_simt(a, s);
+    return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
+}
+
+kvq_status kvq_chunk_attention(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                               const void *q, const void *k_cur, const void *v_cur, int64_t m,
+                               int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                               float softmax_scale, int correction, void *out, float *mass_cached,
+                               void *hip_stream)
+{
+    return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
+                            softmax_scale, correction, out, mass_cached, hip_stream, false);
+}
+
+kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                    const void *q, const void *k_cur, const void *v_cur, int64_t m,
+                                    int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                    float softmax_scale, int correction, void *out, float *mass_cached,
+                                    void *hip_stream)
+{
+    return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
+                            softmax_scale, correction, out, mass_cached, hip_stream, true);
+}
+
+kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count, uint8_t *codes,
+                            float *scales, float *zeros, void *hip_stream)
+{
+    if (!cache || (which != 0 && which != 1) || start < 0 || count < 0) return KVQ_ERR_INVALID_ARG;
+    if (start + count > cache->len) return KVQ_ERR_INVALID_ARG;
+    if (count == 0) return KVQ_OK;
+    const hipError_t e = kvq::launch_export(cache->view, which, start, count, codes, scales, zeros,
+                                            static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
+}
+
+const char *kvq_status_string(kvq_status status)
+{
+    switch (status) {
+        case KVQ_OK: return "ok";
+        case KVQ_ERR_INVALID_ARG: return "invalid argument";
+        case KVQ_ERR_UNSUPPORTED: return "unsupported configuration";
+        case KVQ_ERR_CAPACITY: return "cache capacity exceeded";
+        case KVQ_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *kvq_version(void) { return "0.1"; }
+
+}  // extern "C"

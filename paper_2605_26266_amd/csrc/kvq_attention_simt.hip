@@ -1,0 +1,178 @@
+// fp32 vector-ALU chunk attention: the reference-precision GPU path.
+//
+// Used for KVQ_FP32 caches, for head_dim 64, and by kvq_chunk_attention_fp32.  It follows
+// Alg. 1 of the paper literally in single precision, one workgroup of d threads per
+// (head, query row):
+//   * rotate the query (butterflies in LDS), nu = ||q||^2;
+//   * pass 1: every thread scores a strided subset of the keys (cached keys from their packed
+//     codes, corrected by b = scale^2 * step^2 * nu / 24; current keys from k_cur) to find the
+//     row maximum;
+//   * pass 2: scores again, p = exp(s - max); blocks of d weights go through LDS so that thread c
+//     accumulates output channel c; the cached part is accumulated in the rotated basis and
+//     rotated back before the current part is added.
+// Throughput is a few TFLOP/s at best; the matrix-core kernel is the fast path.
+#include "kvq_internal.h"
+
+namespace kvq {
+namespace {
+
+template <int D> __device__ inline void fwht_lds(float *buf, int c)
+{
+    // In-place Sylvester-Hadamard transform of buf[0..D) by D threads; unnormalised.
+#pragma unroll
+    for (int h = 1; h < D; h <<= 1) {
+        __syncthreads();
+        const float a = buf[c & ~h], b = buf[c | h];
+        __syncthreads();
+        buf[c] = (c & h) ? a - b : a + b;
+    }
+    __syncthreads();
+}
+
+template <int D> __device__ inline float block_reduce(float v, float *scratch, int c, bool is_max)
+{
+    __syncthreads();
+    scratch[c] = v;
+    __syncthreads();
+    for (int s = D / 2; s > 0; s >>= 1) {
+        if (c < s) scratch[c] = is_max ? fmaxf(scratch[c], scratch[c + s]) : scratch[c] + scratch[c + s];
+        __syncthreads();
+    }
+    const float r = scratch[0];
+    __syncthreads();
+    return r;
+}
+
+template <int D, int BITS, typename T>
+__global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
+{
+    constexpr int WPL = D * BITS / 64;
+    constexpr uint32_t MASK = (1u << BITS) - 1u;
+    __shared__ float q_rot[D];   // Hn q
+    __shared__ float q_raw[D];
+    __shared__ float p_blk[D];
+    __shared__ float scratch[D];
+    const CacheView &cv = a.cv;
+    const int c = threadIdx.x;
+    const int head = blockIdx.y;
+    const int64_t row = blockIdx.x;
+    const float norm = D == 64 ? 0.125f : 0.088388347648318f;
+    const float sigma = a.softmax_scale;
+    const float off = code_offset(BITS);
+
+    const T *qp = static_cast<const T *>(a.q) + row * a.stride_token + (int64_t)head * a.stride_head;
+    const float qc = Io<T>::load(qp + c);
+    q_raw[c] = qc;
+    q_rot[c] = qc;
+    fwht_lds<D>(q_rot, c);
+    q_rot[c] *= norm;
+    const float nu = block_reduce<D>(qc * qc, scratch, c, false);
+    const float corr_coef = a.correction ? sigma * sigma * nu * (1.0f / 24.0f) : 0.0f;
+
+    const int64_t meta0 = (int64_t)head * cv.cap_tiles * kTileTokens;
+    const uint32_t *k_head = cv.k_codes + (int64_t)head * cv.cap_tiles * tile_words(D, BITS);
+    const uint32_t *v_head = cv.v_codes + (int64_t)head * cv.cap_tiles * tile_words(D, BITS);
+
+    auto cached_score = [&](int64_t t) -> float {
+        const uint32_t *tile = k_head + (t / kTileTokens) * tile_words(D, BITS);
+        const int tt = (int)(t % kTileTokens);
+        const float scale = cv.k_scale[meta0 + t];
+        const float zero = -cv.k_negzero[meta0 + t] - off;
+        float dot = 0.0f;
+        for (int hh = 0; hh < 2; ++hh) {
+            const uint32_t *slot = tile + (hh * 32 + tt) * WPL;
+            for (int w = 0; w < WPL; ++w) {
+                const uint32_t word = slot[w];
+                for (int j = 0; j < 16 / BITS; ++j) {
+                    const int slab = BITS == 2 ? 2 * w + (j >> 2) : w;
+                    const int ch = 16 * slab + 8 * hh + 2 * (j & 3);
+                    const float c0 = (float)((word >> (BITS * j)) & MASK);
+                    const float c1 = (float)((word >> (BITS * j + 16)) & MASK);
+                    dot = fmaf(q_rot[ch], (c0 - zero) * scale, dot);
+                    dot = fmaf(q_rot[ch + 1], (c1 - zero) * scale, dot);
+                }
+            }
+        }
+        return sigma * dot - corr_coef * scale * scale;
+    };
+    auto current_score = [&](int64_t j) -> float {
+        const T *kp = static_cast<const T *>(a.k_cur) + j * a.stride_token + (int64_t)head * a.stride_head;
+        float dot = 0.0f;
+        for (int ch = 0; ch < D; ++ch) dot = fmaf(q_raw[ch], Io<T>::load(kp + ch), dot);
+        return sigma * dot;
+    };
+
+    // Pass 1: row maximum.
+    float mx = -INFINITY;
+    for (int64_t i = c; i < a.cache_len; i += D) mx = fmaxf(mx, cached_score(a.cache_start + i));
+    for (int64_t j = c; j < a.n_cur; j += D) mx = fmaxf(mx, current_score(j));
+    mx = block_reduce<D>(mx, scratch, c, true);
+
+    // Pass 2: weights and weighted sums.
+    float sum_s = 0.0f, sum_r = 0.0f, acc = 0.0f;
+    for (int64_t base = 0; base < a.cache_len; base += D) {
+        const int64_t i = base + c;
+        const float p = i < a.cache_len ? expf(cached_score(a.cache_start + i) - mx) : 0.0f;
+        sum_s += p;
+        __syncthreads();
+        p_blk[c] = p;
+        __syncthreads();
+        const int cnt = (int)((a.cache_len - base) < D ? (a.cache_len - base) : D);
+        for (int jj = 0; jj < cnt; ++jj) {
+            const int64_t t = a.cache_start + base + jj;
+            int word, shift;
+            value_code_pos(D, BITS, (int)(t % kTileTokens), c, word, shift);
+            const uint32_t w = v_head[(t / kTileTokens) * tile_words(D, BITS) + word];
+            const float code = (float)((w >> shift) & MASK);
+            const float vz = cv.v_zero_off[meta0 + t] - off;
+            acc = fmaf(p_blk[jj], (code - vz) * cv.v_scale[meta0 + t], acc);
+        }
+    }
+    // Rotate the cached part back: out_S = Hn^T acc (Hn symmetric).
+    __syncthreads();
+    scratch[c] = acc;
+    fwht_lds<D>(scratch, c);
+    acc = scratch[c] * norm;
+    __syncthreads();
+    for (int64_t base = 0; base < a.n_cur; base += D) {
+        const int64_t j = base + c;
+        const float p = j < a.n_cur ? expf(current_score(j) - mx) : 0.0f;
+        sum_r += p;
+        __syncthreads();
+        p_blk[c] = p;
+        __syncthreads();
+        const int cnt = (int)((a.n_cur - base) < D ? (a.n_cur - base) : D);
+        for (int jj = 0; jj < cnt; ++jj) {
+            const T *vp = static_cast<const T *>(a.v_cur) + (base + jj) * a.stride_token + (int64_t)head * a.stride_head;
+            acc = fmaf(p_blk[jj], Io<T>::load(vp + c), acc);
+        }
+    }
+    sum_s = block_reduce<D>(sum_s, scratch, c, false);
+    sum_r = block_reduce<D>(sum_r, scratch, c, false);
+    const float inv = 1.0f / (sum_s + sum_r);
+    T *op = static_cast<T *>(a.out) + row * a.stride_token + (int64_t)head * a.stride_head;
+    Io<T>::store(op + c, acc * inv);
+    if (a.mass_cached && c == 0) a.mass_cached[(int64_t)head * a.m + row] = sum_s * inv;
+}
+
+}  // namespace
+
+hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream)
+{
+    const dim3 grid((unsigned)a.m, (unsigned)a.cv.num_heads);
+    const bool bf16 = a.cv.io_dtype == KVQ_BF16;
+#define KVQ_A(D, B)                                                                                         \
+    if (a.cv.head_dim == D && a.cv.bits == B) {                                                             \
+        if (bf16) hipLaunchKernelGGL((attention_simt_kernel<D, B, uint16_t>), grid, dim3(D), 0, stream, a); \
+        else hipLaunchKernelGGL((attention_simt_kernel<D, B, float>), grid, dim3(D), 0, stream, a);         \
+        return hipGetLastError();                                                                           \
+    }
+    KVQ_A(128, 2)
+    KVQ_A(128, 4)
+    KVQ_A(64, 2)
+    KVQ_A(64, 4)
+#undef KVQ_A
+    return hipErrorInvalidValue;
+}
+
+}  // namespace kvq

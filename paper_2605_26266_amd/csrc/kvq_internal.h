@@ -1,0 +1,115 @@
+// Internal declarations shared by the host layer and the gfx950 kernels.
+//
+// Packed cache layout (private to the library)
+// --------------------------------------------
+// Per head the cache holds, for keys and for values, a sequence of 32-token tiles of packed
+// codes plus four float arrays indexed by token.  A tile is 64 "lane slots" of WPL = d*bits/64
+// 32-bit words each, laid out lane-major, so that one wavefront reads a whole tile with a
+// single 16- or 32-byte load per lane and every lane receives exactly the codes its matrix-core
+// operand registers need:
+//
+//  key tile   lane slot = 32*hh + token_in_tile.  The slot holds the codes of the rotated
+//             channels c with bit 3 of c equal to hh, i.e. the eight contraction indices
+//             8*hh..8*hh+7 of every 16-wide slab that this lane feeds to a 32x32x16 MFMA.
+//  value tile lane slot = 32*hh + (channel mod 32).  The slot holds, for the channels
+//             c, c+32, c+64, c+96, the codes of the 16 tokens of the tile with bit 2 of the
+//             token index equal to hh -- the contraction (token) indices this lane feeds to
+//             the P*V MFMA, in the order in which the score MFMA leaves its results in that lane.
+//
+// Inside a word codes sit in pairs (low half-word, high half-word) `bits` apart, so that one
+// shift and one and-or turn a word into a register of two bf16 operands.
+//
+// Per-token metadata: k_scale, k_negzero = -(zero + OFFSET), v_scale, v_zero_off = zero + OFFSET,
+// where OFFSET (4 for 2-bit, 16 for 4-bit codes) is the constant that the bit pattern used for
+// in-register dequantization adds to every code.  Integers of that size are exact in float.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/kvq.h"
+
+namespace kvq {
+
+constexpr int kTileTokens = 32;
+
+struct CacheView {
+    uint32_t *k_codes;   // [H][cap_tiles][64][WPL]
+    uint32_t *v_codes;   // [H][cap_tiles][64][WPL]
+    float *k_scale;      // [H][cap32]
+    float *k_negzero;    // [H][cap32]   -(zero + OFFSET)
+    float *v_scale;      // [H][cap32]
+    float *v_zero_off;   // [H][cap32]   zero + OFFSET
+    int64_t cap_tiles;   // tiles per head
+    int32_t num_heads, head_dim, bits, io_dtype;
+};
+
+__host__ __device__ inline int words_per_lane(int d, int bits) { return d * bits / 64; }
+__host__ __device__ inline int tile_words(int d, int bits) { return d * bits; }  // 64 * WPL
+__host__ __device__ inline float code_offset(int bits) { return bits == 2 ? 4.0f : 16.0f; }
+
+// Word index inside the tile and bit position of the code of (token-in-tile t, rotated channel c).
+__host__ __device__ inline void key_code_pos(int d, int bits, int t, int c, int &word, int &shift)
+{
+    const int slab = c >> 4, hh = (c >> 3) & 1, reg = (c >> 1) & 3, e = c & 1;
+    const int lane = hh * 32 + t;
+    int q, j;
+    if (bits == 2) { q = slab >> 1; j = 4 * (slab & 1) + reg; }
+    else           { q = slab;      j = reg; }
+    word = lane * words_per_lane(d, bits) + q;
+    shift = bits * j + 16 * e;
+}
+
+__host__ __device__ inline void value_code_pos(int d, int bits, int t, int c, int &word, int &shift)
+{
+    const int blk = c >> 5, r = c & 31;
+    const int s = t >> 4, g = (t >> 3) & 1, hh = (t >> 2) & 1, x = (t >> 1) & 1, e = t & 1;
+    const int reg = 2 * g + x;
+    const int lane = hh * 32 + r;
+    int q, j;
+    if (bits == 2) { q = blk;         j = 4 * s + reg; }
+    else           { q = 2 * blk + s; j = reg; }
+    word = lane * words_per_lane(d, bits) + q;
+    shift = bits * j + 16 * e;
+}
+
+// bf16 <-> float on raw bit patterns (round to nearest even on the way down).
+__device__ inline float bf16_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ inline uint16_t float_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Io;
+template <> struct Io<float> {
+    __device__ static float load(const float *p) { return *p; }
+    __device__ static void store(float *p, float v) { *p = v; }
+};
+template <> struct Io<uint16_t> {
+    __device__ static float load(const uint16_t *p) { return bf16_to_float(*p); }
+    __device__ static void store(uint16_t *p, float v) { *p = float_to_bf16(v); }
+};
+
+// Launchers implemented in the kernel translation units.  All return hipError_t of the launch.
+hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
+                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head,
+                                  hipStream_t stream);
+hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
+                         float *scales, float *zeros, hipStream_t stream);
+
+struct AttentionArgs {
+    CacheView cv;
+    int64_t cache_start, cache_len;
+    const void *q, *k_cur, *v_cur;
+    int64_t m, n_cur, stride_token, stride_head;
+    float softmax_scale;
+    int correction;
+    void *out;
+    float *mass_cached;
+};
+hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream);
+hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream);
+
+}  // namespace kvq

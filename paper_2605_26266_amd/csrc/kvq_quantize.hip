@@ -1,0 +1,290 @@
+// Rotate + quantize + pack (kvq_quantize_append) and the canonical export (kvq_cache_export).
+//
+// One workgroup of 256 threads owns one (head, 32-token tile).  Eight lanes share a token
+// vector, so the 256 threads hold the 32 key vectors of the tile in one pass and the 32 value
+// vectors in a second pass.  Per vector:
+//   1. load d elements (coalesced: 8 lanes x 16 elements at d = 128), widen to double;
+//   2. Sylvester-Hadamard transform as log2(d) butterfly stages -- the first log2(d/8) inside
+//      the lane, the last three across the 8 lanes.  Every partial sum of BF16 inputs is exact
+//      in double, so the result does not depend on the order of the additions;
+//   3. min / max over the vector, then the round-to-nearest rule of Eq. 1 of the paper in a
+//      fixed sequence of IEEE double operations (this file is compiled with contraction off);
+//   4. keys: each lane ORs its codes into the words of the tile it feeds and stores them;
+//      values: codes go to LDS, then each thread assembles whole words of the token-major
+//      ("transposed") value tile and stores them.  A tile that an earlier append filled partly is
+//      merged word by word.
+// The kernel is bound by HBM traffic (d*elt bytes in, d*bits/8 + 8 bytes out, per vector).
+#include "kvq_internal.h"
+
+namespace kvq {
+namespace {
+
+template <typename T> struct Vec;
+template <> struct Vec<uint16_t> {  // bf16
+    template <int N> __device__ static void load(const uint16_t *p, double (&x)[N])
+    {
+        static_assert(N % 8 == 0, "");
+#pragma unroll
+        for (int i = 0; i < N / 8; ++i) {
+            const uint4 w = reinterpret_cast<const uint4 *>(p)[i];
+            const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[8 * i + 2 * j] = (double)__uint_as_float(ws[j] << 16);
+                x[8 * i + 2 * j + 1] = (double)__uint_as_float(ws[j] & 0xffff0000u);
+            }
+        }
+    }
+};
+template <> struct Vec<float> {
+    template <int N> __device__ static void load(const float *p, double (&x)[N])
+    {
+        static_assert(N % 4 == 0, "");
+#pragma unroll
+        for (int i = 0; i < N / 4; ++i) {
+            const float4 w = reinterpret_cast<const float4 *>(p)[i];
+            x[4 * i] = (double)w.x;
+            x[4 * i + 1] = (double)w.y;
+            x[4 * i + 2] = (double)w.z;
+            x[4 * i + 3] = (double)w.w;
+        }
+    }
+};
+
+template <int D, int BITS, typename T>
+__global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, const T *__restrict__ k,
+                                                             const T *__restrict__ v, int64_t old_len,
+                                                             int64_t n_tokens, int64_t stride_token,
+                                                             int64_t stride_head)
+{
+    constexpr int EPL = D / 8;            // elements per lane
+    constexpr int WPL = D * BITS / 64;    // words per lane slot
+    constexpr int L = (1 << BITS) - 1;
+    constexpr int CPW = 32 / BITS;        // codes per word
+    __shared__ uint8_t v_stage[kTileTokens][D];
+
+    const int head = blockIdx.y;
+    const int64_t tile = old_len / kTileTokens + blockIdx.x;
+    const int64_t tile_t0 = tile * kTileTokens;
+    const int64_t lo_t = old_len > tile_t0 ? old_len : tile_t0;                    // first new token here
+    const int64_t end_all = old_len + n_tokens;
+    const int64_t hi_t = end_all < tile_t0 + kTileTokens ? end_all : tile_t0 + kTileTokens;
+    const int row = threadIdx.x >> 3, l8 = threadIdx.x & 7;
+    const int64_t t = tile_t0 + row;
+    const bool valid = t >= lo_t && t < hi_t;
+    const int64_t meta_idx = (int64_t)head * cv.cap_tiles * kTileTokens + t;
+    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    const double norm = D == 64 ? 0.125 : 0.08838834764831845;  // 1/sqrt(d) rounded to double
+
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        double x[EPL];
+        if (valid) {
+            const T *src = (pass == 0 ? k : v) + (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * EPL;
+            Vec<T>::template load<EPL>(src, x);
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) x[i] = 0.0;
+        }
+        // Butterflies inside the lane: channel bits 0 .. log2(EPL)-1.
+#pragma unroll
+        for (int h = 1; h < EPL; h <<= 1) {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) {
+                if ((i & h) == 0) {
+                    const double a = x[i], b = x[i + h];
+                    x[i] = a + b;
+                    x[i + h] = a - b;
+                }
+            }
+        }
+        // Butterflies across the 8 lanes of the vector: the upper lane of a pair gets a' = partner - own.
+#pragma unroll
+        for (int msk = 1; msk < 8; msk <<= 1) {
+            const bool upper = (l8 & msk) != 0;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) {
+                const double other = __shfl_xor(x[i], msk);
+                x[i] = upper ? other - x[i] : x[i] + other;
+            }
+        }
+        double lo = x[0], hi = x[0];
+#pragma unroll
+        for (int i = 1; i < EPL; ++i) {
+            lo = x[i] < lo ? x[i] : lo;
+            hi = x[i] > hi ? x[i] : hi;
+        }
+#pragma unroll
+        for (int msk = 1; msk < 8; msk <<= 1) {
+            const double olo = __shfl_xor(lo, msk), ohi = __shfl_xor(hi, msk);
+            lo = olo < lo ? olo : lo;
+            hi = ohi > hi ? ohi : hi;
+        }
+        if (hi == lo) {  // constant vector: widen the range to include 0
+            lo = lo > 0.0 ? 0.0 : lo;
+            hi = hi < 0.0 ? 0.0 : hi;
+        }
+        const bool degenerate = hi == lo;  // all-zero vector
+        const double range = hi - lo;
+        const double inv = degenerate ? 0.0 : (double)L / range;
+        const double step = degenerate ? 0.0 : range / (double)L;
+        const double z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+        int code[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            double c = __builtin_rint(x[i] * inv) + z;
+            c = c < 0.0 ? 0.0 : c;
+            c = c > (double)L ? (double)L : c;
+            code[i] = (int)c;
+        }
+        const float scale = (float)(step * norm);
+        const float zero = (float)z;
+
+        const bool tail = t >= hi_t;  // slot of this tile that no append has reached yet: keep it finite
+        if (pass == 0) {
+            // The lane holds rotated channels EPL*l8 .. EPL*l8+EPL-1: one 16-wide slab (d = 128) or half
+            // a slab (d = 64).  Place its codes at their final bit positions inside the word(s) they share.
+            const int slab = (l8 * EPL) >> 4;
+            const int lane_shift = BITS == 2 ? 8 * (slab & 1) : 0;
+            const int q = BITS == 2 ? slab >> 1 : slab;
+            uint32_t mine[2] = {0u, 0u};
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) {
+                const int hh_i = D == 128 ? (i >> 3) & 1 : 0;  // d = 64: all eight channels share one half
+                mine[hh_i] |= (uint32_t)code[i] << (BITS * ((i >> 1) & 3) + 16 * (i & 1));
+            }
+            mine[0] <<= lane_shift;
+            mine[1] <<= lane_shift;
+            if (BITS == 2) {  // a 2-bit word spans two slabs: merge with the lane that holds the other one
+                constexpr int partner = D == 128 ? 1 : 2;
+                mine[0] |= __shfl_xor(mine[0], partner);
+                mine[1] |= __shfl_xor(mine[1], partner);
+            }
+            if (valid || tail) {
+                if (D == 128) {
+                    if (BITS == 4) {
+                        k_tile[row * WPL + q] = mine[0];
+                        k_tile[(32 + row) * WPL + q] = mine[1];
+                    } else {
+                        const int hh = l8 & 1;
+                        k_tile[(hh * 32 + row) * WPL + q] = hh ? mine[1] : mine[0];
+                    }
+                } else {
+                    const int hh = l8 & 1;
+                    if (BITS == 4 || (l8 & 2) == 0) k_tile[(hh * 32 + row) * WPL + q] = mine[0];
+                }
+                if (l8 == 2) cv.k_scale[meta_idx] = scale;
+                if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) v_stage[row][l8 * EPL + i] = (uint8_t)code[i];
+            if (valid || tail) {
+                if (l8 == 2) cv.v_scale[meta_idx] = scale;
+                if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+            }
+        }
+    }
+    __syncthreads();
+    // Assemble the value tile: word (lane slot, q) gathers CPW codes of one channel.
+    const int t_keep = (int)(lo_t - tile_t0);   // tokens below this index were written by an earlier append
+    const int t_new_end = (int)(hi_t - tile_t0);
+    for (int w = threadIdx.x; w < 64 * WPL; w += 256) {
+        const int lane = w / WPL, q = w % WPL;
+        const int hh = lane >> 5, r = lane & 31;
+        const int blk = BITS == 2 ? q : q >> 1;
+        const int c = 32 * blk + r;
+        uint32_t word = 0u, keep = 0u;
+#pragma unroll
+        for (int p = 0; p < CPW; ++p) {
+            const int j = p % (CPW / 2), e = p / (CPW / 2);
+            const int s = BITS == 2 ? (j >> 2) : (q & 1);
+            const int reg = j & 3;
+            const int tok = 16 * s + 8 * (reg >> 1) + 4 * hh + 2 * (reg & 1) + e;
+            const int shift = BITS * j + 16 * e;
+            if (tok < t_keep) keep |= (uint32_t)L << shift;
+            else if (tok < t_new_end) word |= (uint32_t)v_stage[tok][c] << shift;
+        }
+        if (keep) word |= v_tile[w] & keep;
+        v_tile[w] = word;
+    }
+}
+
+template <int D, int BITS>
+__global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int64_t start, int64_t count,
+                                                  uint8_t *codes, float *scales, float *zeros)
+{
+    const int head = blockIdx.y;
+    const int c = threadIdx.x;
+    for (int64_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const int64_t t = start + i;
+        const int64_t tile = t / kTileTokens;
+        const int tt = (int)(t % kTileTokens);
+        const uint32_t *base = (which == 0 ? cv.k_codes : cv.v_codes) +
+                               ((int64_t)head * cv.cap_tiles + tile) * tile_words(D, BITS);
+        int word, shift;
+        if (which == 0) key_code_pos(D, BITS, tt, c, word, shift);
+        else value_code_pos(D, BITS, tt, c, word, shift);
+        if (codes) codes[((int64_t)head * count + i) * D + c] = (uint8_t)((base[word] >> shift) & ((1u << BITS) - 1u));
+        if (c == 0) {
+            const int64_t mi = (int64_t)head * cv.cap_tiles * kTileTokens + t;
+            if (scales) scales[(int64_t)head * count + i] = which == 0 ? cv.k_scale[mi] : cv.v_scale[mi];
+            if (zeros)
+                zeros[(int64_t)head * count + i] =
+                    which == 0 ? -cv.k_negzero[mi] - code_offset(BITS) : cv.v_zero_off[mi] - code_offset(BITS);
+        }
+    }
+}
+
+template <int D, int BITS, typename T>
+hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t old_len, int64_t n, int64_t st,
+                    int64_t sh, hipStream_t stream)
+{
+    const int64_t first_tile = old_len / kTileTokens;
+    const int64_t last_tile = (old_len + n - 1) / kTileTokens;
+    const dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)cv.num_heads);
+    hipLaunchKernelGGL((quantize_append_kernel<D, BITS, T>), grid, dim3(256), 0, stream, cv,
+                       static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
+                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head,
+                                  hipStream_t stream)
+{
+    const bool bf16 = cv.io_dtype == KVQ_BF16;
+#define KVQ_Q(D, B)                                                                                             \
+    if (cv.head_dim == D && cv.bits == B)                                                                       \
+        return bf16 ? launch_q<D, B, uint16_t>(cv, k, v, old_len, n_tokens, stride_token, stride_head, stream)  \
+                    : launch_q<D, B, float>(cv, k, v, old_len, n_tokens, stride_token, stride_head, stream);
+    KVQ_Q(128, 2)
+    KVQ_Q(128, 4)
+    KVQ_Q(64, 2)
+    KVQ_Q(64, 4)
+#undef KVQ_Q
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
+                         float *scales, float *zeros, hipStream_t stream)
+{
+    const unsigned gx = (unsigned)(count < 4096 ? count : 4096);
+    const dim3 grid(gx, (unsigned)cv.num_heads);
+#define KVQ_E(D, B)                                                                                        \
+    if (cv.head_dim == D && cv.bits == B) {                                                                \
+        hipLaunchKernelGGL((export_kernel<D, B>), grid, dim3(D), 0, stream, cv, which, start, count, codes, \
+                           scales, zeros);                                                                 \
+        return hipGetLastError();                                                                          \
+    }
+    KVQ_E(128, 2)
+    KVQ_E(128, 4)
+    KVQ_E(64, 2)
+    KVQ_E(64, 4)
+#undef KVQ_E
+    return hipErrorInvalidValue;
+}
+
+}  // namespace kvq

@@ -1,0 +1,177 @@
+"""GPU parity of kvq_chunk_attention against the CPU oracle (outputs and attention masses)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import parity
+    return parity
+
+
+def _cached(w, heads=None):
+    from paper_2605_26266_amd import workloads as wl
+    ks, vs = zip(*[wl.chunk_kv(w, c, heads) for c in range(w.cached_chunks)])
+    return np.concatenate(ks), np.concatenate(vs)
+
+
+def _fill(P, cache, w):
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    for c in range(w.cached_chunks):
+        k, v = wl.chunk_kv(w, c)
+        B.kvq_quantize_append(cache, P.to_dev(k, w.io_dtype), P.to_dev(v, w.io_dtype))
+
+
+@pytest.mark.parametrize("correction", [1, 0])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_tiny_fp32(P, bits, correction):
+    """Tiny config, fp32 I/O: the fp32 vector kernel against the double oracle, all rows."""
+    import oracle
+    from paper_2605_26266_amd import workloads as wl
+    w = wl.WORKLOADS["tiny"].with_bits(bits)
+    cache = P.make_cache(w, w.cached_tokens)
+    _fill(P, cache, w)
+    kc, vc = _cached(w)
+    kr, vr = wl.chunk_kv(w, w.cached_chunks)
+    q = wl.chunk_q(w)
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "fp32", correction=correction)
+    err = P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_FP32, "tiny")
+    print("tiny bits=%d corr=%d: max err %.2e, mean P_S %.4f" % (bits, correction, err, mass.mean()))
+
+
+@pytest.mark.parametrize("fp32_kernel", [True, False])
+@pytest.mark.parametrize("correction", [1, 0])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_small_all_rows(P, bits, correction, fp32_kernel):
+    """Small config in full: 8 heads, 4096 cached + 1024 current tokens, every query row."""
+    import oracle
+    from paper_2605_26266_amd import workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    cache = P.make_cache(w, w.cached_tokens)
+    _fill(P, cache, w)
+    kc, vc = _cached(w)
+    kr, vr = wl.chunk_kv(w, w.cached_chunks)
+    q = wl.chunk_q(w)
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction, fp32_kernel=fp32_kernel)
+    err = P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "small")
+    print("small bits=%d corr=%d fp32=%d: max err %.2e" % (bits, correction, fp32_kernel, err))
+
+
+RAGGED = [
+    # (m, cache_start, cache_len, n_cur)
+    (1, 0, 1, 0),
+    (1, 0, 0, 1),
+    (7, 0, 33, 5),
+    (64, 3, 61, 64),
+    (65, 31, 34, 31),
+    (130, 32, 200, 97),
+    (257, 5, 1000, 0),
+    (300, 0, 0, 333),
+    (300, 17, 777, 129),
+    (511, 64, 1024, 513),
+]
+
+
+@pytest.mark.parametrize("fp32_kernel", [True, False])
+@pytest.mark.parametrize("bits", [2, 4])
+def test_ragged_shapes_and_windows(P, bits, fp32_kernel):
+    """Row tails, key tails, windows that start and end inside a tile, empty cache, empty current block."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads = 3
+    cache = P.make_cache(w, 1100, heads=heads)
+    k0, v0 = wl.chunk_kv(w, 0, heads=range(heads))
+    k1, v1 = wl.chunk_kv(w, 1, heads=range(heads))
+    kc, vc = np.concatenate([k0, k1])[:1100], np.concatenate([v0, v1])[:1100]
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr_all, vr_all = wl.chunk_kv(w, 2, heads=range(heads))
+    q_all = wl.chunk_q(w, heads=range(heads))
+    for (m, start, clen, ncur) in RAGGED:
+        q, kr, vr = q_all[:m], kr_all[:ncur], vr_all[:ncur]
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc[start:start + clen], vc[start:start + clen], kr, vr, bits, 1)
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=start, cache_len=clen,
+                                        fp32_kernel=fp32_kernel)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "ragged %s" % ((m, start, clen, ncur),))
+
+
+def test_softmax_scale_and_large_queries(P):
+    """A caller-chosen softmax scale enters the correction squared; big query norms make b matter."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads = 2
+    cache = P.make_cache(w, 512, heads=heads)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=512)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=256)
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:256] * np.float32(2.0))
+    for sigma in (0.05, 0.125):
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1, sigma=sigma)
+        off, mass_off, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 0, sigma=sigma)
+        assert np.max(np.abs(mass_ref - mass_off)) > 0.02          # the correction is not a no-op here
+        for fp32_kernel in (True, False):
+            out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", softmax_scale=sigma, fp32_kernel=fp32_kernel)
+            P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "sigma=%g" % sigma)
+
+
+def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None):
+    """Full-size GPU run as the benchmark launches it; oracle on sampled heads x sampled rows."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS[name].with_bits(bits)
+    n_chunks = w.cached_chunks if cached_chunks is None else cached_chunks
+    cache = P.make_cache(w, n_chunks * w.chunk_tokens)
+    ks, vs = [], []
+    for c in range(n_chunks):
+        k, v = wl.chunk_kv(w, c)
+        B.kvq_quantize_append(cache, P.to_dev(k, "bf16"), P.to_dev(v, "bf16"))
+        ks.append(k[:, heads].copy())
+        vs.append(v[:, heads].copy())
+    kc, vc = np.concatenate(ks), np.concatenate(vs)
+    kr, vr = wl.chunk_kv(w, w.cached_chunks)
+    q = wl.chunk_q(w)
+    rows = wl.sample_rows(w, n_rows)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction)
+    ref, mass_ref, _ = oracle.chunk_attention(q[rows][:, heads], kc, vc, kr[:, heads], vr[:, heads], bits, correction)
+    return P.assert_attention_close(out[rows][:, heads], mass[heads][:, rows], ref, mass_ref, P.TOL_OUT_BF16,
+                                    "%s int%d" % (name, bits))
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_mid_sampled_rows(P, bits):
+    err = _sampled_case(P, "mid", bits, 48, [0, 23])
+    print("mid int%d: max err %.2e" % (bits, err))
+
+
+@pytest.mark.parametrize("correction", [1, 0])
+def test_large_sampled_rows(P, correction):
+    err = _sampled_case(P, "large", 2, 32, [5, 47], correction)
+    print("large corr=%d: max err %.2e" % (correction, err))
+
+
+def test_argument_errors(P):
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    cache = P.make_cache(w, 64)
+    k, v = wl.chunk_kv(w, 0, n_tokens=64)
+    B.kvq_quantize_append(cache, P.to_dev(k, "bf16"), P.to_dev(v, "bf16"))
+    q = P.to_dev(wl.chunk_q(w)[:16], "bf16")
+    out = torch.empty_like(q)
+    with pytest.raises(B.KvqError) as e:
+        B.kvq_chunk_attention(cache, 0, 65, q, None, None, out)      # window beyond the cache
+    assert e.value.status == B.KVQ_ERR_INVALID_ARG
+    with pytest.raises(B.KvqError):
+        B.kvq_chunk_attention(cache, 0, 0, q, None, None, out)       # no keys at all
+    with pytest.raises(B.KvqError):
+        B.kvq_chunk_attention(cache, 0, 64, q, None, None, q)        # out aliases q
+    with pytest.raises(B.KvqError):
+        B.kvq_chunk_attention(cache, 0, 64, q, None, None, out, correction=2)
+    B.kvq_chunk_attention(cache, 0, 64, q[:0], None, None, out[:0])   # m == 0 is a no-op

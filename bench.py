@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-KV chunk-attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input of the Large
+configuration (48 heads, head_dim 128, 4096-token chunk, 16 cached chunks at INT2):
+    kvq_quantize_append   of the newest cached chunk (the cache is truncated to 15 chunks first,
+                          a host-side counter change), then
+    kvq_chunk_attention   of the current chunk's 4096 queries over the 65536 cached tokens plus
+                          the 4096 unquantized current tokens, with the Taylor correction on.
+Inputs are resident in HBM before the timed region.  `value` is the algorithmic attention work
+4*H*M*(N_S+N_R)*d per step divided by the whole step time (append included).
+
+Prints ONE JSON line.  Extra fields: per-kernel timings from HIP events recorded on the launch
+stream inside the timed region, the correction overhead (corrected vs uncorrected kernel,
+interleaved), the roofline of the dominant kernel, and the CPU oracle timed on the host cores on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/f16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", choices=["small", "mid", "large"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=768, help="query rows of one head given to the CPU oracle")
+    return ap.parse_args()
+
+
+def cpu_baseline(w, wl, rows_wanted):
+    """The oracle, as it stands, on one head and a seeded subset of query rows (all keys)."""
+    import oracle
+    head = [0]
+    rows = wl.sample_rows(w, rows_wanted)
+    ks, vs = zip(*[wl.chunk_kv(w, c, head) for c in range(w.cached_chunks)])
+    kc, vc = np.concatenate(ks)[:, 0].astype(np.float64), np.concatenate(vs)[:, 0].astype(np.float64)
+    kr, vr = wl.chunk_kv(w, w.cached_chunks, head)
+    q = wl.chunk_q(w, head)[rows][:, 0]
+    t0 = time.perf_counter()
+    k_codes, k_scale, k_zero = oracle.quantize(kc, w.bits)
+    v_codes, v_scale, v_zero = oracle.quantize(vc, w.bits)
+    t_quant = time.perf_counter() - t0
+    khat, vhat = oracle.dequantize(k_codes, k_scale, k_zero), oracle.dequantize(v_codes, v_scale, v_zero)
+    t0 = time.perf_counter()
+    oracle.attention(q, khat, k_scale, vhat, kr[:, 0], vr[:, 0], correction=1)
+    t_att = time.perf_counter() - t0
+    n_keys = kc.shape[0] + kr.shape[0]
+    flop = 4.0 * len(rows) * n_keys * w.head_dim
+    quant_rows = 2 * kc.shape[0]
+    return {
+        "value": flop / t_att / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": "attention: 1 head x %d seeded query rows x all %d keys of the %s config (%.1f s); "
+                  "quantizer: %d vectors of that head (%.1f s)" % (len(rows), n_keys, w.name, t_att, quant_rows, t_quant),
+        "attention_seconds": t_att,
+        "quantize_rows_per_s": quant_rows / t_quant,
+        "quantize_gb_per_s_equiv": quant_rows * (w.quantize_bytes(1) / (2 * w.num_heads)) / t_quant / 1e9,
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (heads shard with no "
+              "communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_26266_amd import binding as B
+    from paper_2605_26266_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()  # fail loudly when the library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    n_cached = w.cached_chunks
+
+    def up(x):
+        return torch.from_numpy(x).to(dev).to(torch.bfloat16)
+
+    # ---- resident inputs: the cache filled with chunks 0..n-2, chunk n-1 kept in bf16 for the timed append
+    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16), dev)
+    for c in range(n_cached - 1):
+        k, v = wl.chunk_kv(w, c)
+        B.kvq_quantize_append(cache, up(k), up(v))
+    k_new, v_new = (up(x) for x in wl.chunk_kv(w, n_cached - 1))
+    k_cur, v_cur = (up(x) for x in wl.chunk_kv(w, n_cached))
+    q = up(wl.chunk_q(w))
+    out = torch.empty_like(q)
+    mass = torch.empty((w.num_heads, w.chunk_tokens), dtype=torch.float32, device=dev)
+    keep = (n_cached - 1) * w.chunk_tokens
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        B.kvq_cache_truncate(cache, keep)
+        if events:
+            events[0].record()
+        B.kvq_quantize_append(cache, k_new, v_new)
+        if events:
+            events[1].record()
+        B.kvq_chunk_attention(cache, 0, w.cached_tokens, q, k_cur, v_cur, out, mass, 0.0, 1)
+        if events:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    t_quant = np.array([e[0].elapsed_time(e[1]) for e in ev])   # ms
+    t_att = np.array([e[1].elapsed_time(e[2]) for e in ev])
+
+    # ---- correction overhead: corrected and uncorrected kernels interleaved run by run
+    reps = max(5, args.steps // 2)
+    pair = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(reps)]
+    for p in pair:
+        p[0].record()
+        B.kvq_chunk_attention(cache, 0, w.cached_tokens, q, k_cur, v_cur, out, mass, 0.0, 1)
+        p[1].record()
+        B.kvq_chunk_attention(cache, 0, w.cached_tokens, q, k_cur, v_cur, out, mass, 0.0, 0)
+        p[2].record()
+    torch.cuda.synchronize()
+    t_on = np.median([p[0].elapsed_time(p[1]) for p in pair])
+    t_off = np.median([p[1].elapsed_time(p[2]) for p in pair])
+
+    flop = w.attention_flop
+    att_ms = float(np.mean(t_att))
+    quant_ms = float(np.mean(t_quant))
+    att_tflops = flop / (att_ms * 1e-3) / 1e12
+    result = {
+        "metric": "corrected INT2-KV chunk-attention TFLOP/s (+ % MFMA peak); quantize GB/s",
+        "value": flop / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d heads, head_dim %d, chunk %d tokens, %d cached chunks (%d tokens) INT%d "
+                               "per-token asymmetric after Hadamard rotation, correction on"
+                               % (w.name, w.num_heads, w.head_dim, w.chunk_tokens, n_cached, w.cached_tokens, w.bits),
+                   "step": "quantize_append(1 chunk) + chunk_attention"},
+        "attention_ms": att_ms,
+        "attention_tflops": att_tflops,
+        "pct_mfma_peak": 100.0 * att_tflops / MFMA_PEAK_TFLOPS,
+        "quantize_ms": quant_ms,
+        "quantize_gb_per_s": w.quantize_bytes() / (quant_ms * 1e-3) / 1e9,
+        "quantize_pct_hbm_peak": 100.0 * w.quantize_bytes() / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "correction_overhead_pct": 100.0 * (t_on / t_off - 1.0),
+        "attention_ms_uncorrected": float(t_off),
+        "roofline": {
+            "kernel": "attention_mfma_kernel<2, true>",
+            "bound": "mfma",
+            "achieved": att_tflops,
+            "peak": MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s",
+            "frac": att_tflops / MFMA_PEAK_TFLOPS,
+            "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_rows)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

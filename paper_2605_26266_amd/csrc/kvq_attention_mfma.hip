@@ -1,40 +1,50 @@
 // Matrix-core chunk attention for gfx950: BF16 I/O, head_dim 128, 2- or 4-bit cache.
 //
 // Work split.  One workgroup = 4 wavefronts = 256 query rows of one head; each wavefront owns
-// 64 rows (two 32-row blocks) for the whole key loop, so the waves only meet at the barriers
-// of the staging pipeline.  Everything is computed transposed,
+// 64 rows (two 32-row blocks) for the whole key loop, so the waves only meet at one barrier per
+// 128 staged keys.  Everything is computed transposed,
 //     S^T = K Q~^T           (A operand: keys,     B operand: queries)
 //     O^T = V^T P^T          (A operand: channels, B operand: queries)
-// with v_mfma_f32_32x32x16_bf16.  In that orientation a lane owns one query row (row = lane
-// mod 32) of every result tile, so the softmax row maximum and row sum are reductions inside a
-// lane plus one exchange between the two lane halves, and the probabilities the score MFMA
-// leaves in a lane are exactly that lane's B operand of the P*V MFMA -- no shuffle, no LDS round
-// trip for P.
+// with v_mfma_f32_32x32x16.  In that orientation a lane owns one query row (row = lane mod 32) of
+// every result tile, so the softmax row maximum and row sum are reductions inside a lane plus one
+// exchange between the two lane halves, and the probabilities the score MFMA leaves in a lane are
+// exactly that lane's B operand of the P*V MFMA -- no shuffle, no LDS round trip for P.
 //
 // Cached keys/values (Alg. 1 of the paper, cached block).  Packed tiles (see kvq_internal.h) are
-// staged through LDS 128 keys at a time, double buffered.  A lane pulls its 16 or 32 bytes of codes
-// and turns every word into MFMA operand registers with one shift and one and-or per register: the
-// code lands in the top mantissa bits of a 16-bit float whose exponent makes the value OFFSET + code
-// (4 + code for 2 bits, 16 + code for 4 bits).  Key codes and the rotated query use f16 (same MFMA
-// rate as bf16, three more significant bits for the query, codes exact either way); value codes and
-// probabilities use bf16 (its range is needed for p * value-scale).  Per-token scale and zero-point never touch the
-// operands: with one (scale, zero) per token
+// staged through LDS 128 keys at a time (three buffers, one barrier per stage).  A lane pulls its 16
+// or 32 bytes of codes and turns every word into MFMA operand registers with one shift and one
+// and-or per register: the code lands in the top mantissa bits of a 16-bit float whose exponent makes
+// the value OFFSET + code (4 + code for 2 bits, 16 + code for 4 bits).  Key codes and the rotated
+// query use f16 (same MFMA rate as bf16, three more significant bits; codes are exact either way) and
+// the query is carried as a high + low f16 pair; value codes and probabilities use bf16 (its range is
+// needed for p * value-scale).  Per-token scale and zero-point never touch the operands: with one
+// (scale, zero) per token
 //     s_mi = scale_i * ( q~_m . (OFFSET + code_i)  -  (OFFSET + z_i) * sum_c q~_mc  -  scale_i * nu'_m )
-// where q~ already carries softmax_scale * log2(e) / sqrt(d), and nu'_m = softmax_scale^2 *
-// log2(e) * ||q_m||^2 / 24 is the Taylor correction b (Eq. 13 / Eq. 15 with one group) in units of
-// scale_i^2 -- one fused multiply-add per cached score, computed from ||q_m||^2 once per row.
-// On the value side the value scale is folded into the probability before it is rounded to bf16,
-// and the zero-point/OFFSET term is a per-row scalar tau_m = sum_i p'_mi (OFFSET + z_i), accumulated
-// from the rounded probabilities so that it cancels exactly.  The cached part of O lives in the
-// rotated basis; when the cached keys are done the accumulators are rotated back in registers
-// (six butterfly stages inside the lane, one between the lane halves) and the loop continues with
-// the current chunk in the original basis.
+// where q~ already carries softmax_scale * log2(e) / sqrt(d) and nu'_m = softmax_scale^2 * log2(e) *
+// ||q_m||^2 / 24 is the Taylor correction b (Eq. 13 / Eq. 15 with one group) in units of scale_i^2,
+// from ||q_m||^2 computed once per row.  The two rank-one terms ride on the matrix cores as well: the
+// loader turns (zero, scale, window mask) of each key into one more 16-wide A operand, the row
+// constants (sum of q~, nu') form its B operand, split into bf16 pieces that add up to fp32 accuracy.
+// The correction therefore costs no vector instruction at all; what is left per score is one fused
+// multiply-add (scale, minus the reference maximum), the exponential and the P*V bookkeeping.
+// On the value side the value scale is folded into the probability before it is rounded to bf16, and
+// the zero-point/OFFSET term is a per-row scalar tau_m = sum_i p'_mi (OFFSET + z_i), accumulated from
+// the rounded probabilities (dot2 on bf16 pairs) so that it cancels exactly.  The cached part of O
+// lives in the rotated basis; when the cached keys are done the accumulators are rotated back in
+// registers (six butterfly stages inside the lane, one between the lane halves) and the loop continues
+// with the current chunk in the original basis.
+//
+// Software pipeline.  One iteration issues the score MFMAs of tile t+1 next to the exponentials of
+// tile t, then the P*V MFMAs of tile t next to the scaling of the scores of tile t+1, so that a single
+// wave per SIMD keeps the matrix pipe and the vector ALU busy at the same time.
+//
+// Online softmax.  Each row keeps a reference maximum m and the partial sums l_S, l_R.  The reference
+// only moves when a tile's maximum exceeds it by more than 2^8 (results stay exact: a stale reference
+// just scales numerator and denominator alike); that rare case leaves the fast loop, rescales, and
+// re-enters, which keeps the accumulators pinned in their registers inside the loop.
 //
 // Current keys/values (unquantized block).  K rows are read straight into A operands; V tiles are
 // transposed through LDS (token-major operands); scores get no correction.
-//
-// The running maximum is exact; accumulators are only rescaled on tiles where some row's maximum
-// actually grows.
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -55,30 +65,37 @@ constexpr int kRowsPerWave = 64;
 constexpr int kRowsPerBlock = kWaves * kRowsPerWave;  // 256
 constexpr int kStageTiles = 4;
 constexpr int kStageKeys = kStageTiles * kTileTokens;  // 128
+constexpr int kBuffers = 3;
 constexpr int kQRowWords = 68;    // 64 words of f16 pairs + 4 words padding (bank spread)
 constexpr int kVtRowWords = 18;   // 32 tokens of bf16 = 16 words + 2 words padding
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRescaleThreshold = 8.0f;   // log2 units a tile may exceed the reference by
+constexpr float kMaskBias = -1.0e30f;
 
+// Word offsets inside one stage buffer.
 template <int BITS> struct Stage {
     static constexpr int WPL = D * BITS / 64;
-    static constexpr int kCodeWords = kStageTiles * 64 * WPL;
-    static constexpr int kWords = 2 * kCodeWords + 4 * kStageKeys;  // K codes, V codes, 4 float arrays
+    static constexpr int kCodeWords = kStageTiles * 64 * WPL;   // per tensor
+    static constexpr int kK = 0;
+    static constexpr int kV = kCodeWords;
+    static constexpr int kCop = 2 * kCodeWords;                 // [tile][lane][4]  constant-term A operand
+    static constexpr int kKScale = kCop + kStageTiles * 64 * 4; // [tile][hh][16]   float
+    static constexpr int kVScale = kKScale + kStageKeys;        // [tile][hh][16]   float
+    static constexpr int kVzHi = kVScale + kStageKeys;          // [tile][hh][8]    bf16 pairs
+    static constexpr int kVzLo = kVzHi + kStageKeys / 2;
+    static constexpr int kWords = kVzLo + kStageKeys / 2;
 };
 
 template <int BITS> constexpr size_t lds_bytes()
 {
-    // two stage buffers | per-wave query staging (also reused for the V^T tiles) | per-row scalars
-    return sizeof(uint32_t) * (2 * Stage<BITS>::kWords + kRowsPerBlock * kQRowWords + 2 * kRowsPerBlock);
+    // stage buffers | per-wave low parts of q~ (also staging for the query prep and the V^T tiles) | row scalars
+    return sizeof(uint32_t) * (kBuffers * Stage<BITS>::kWords + kRowsPerBlock * kQRowWords + 2 * kRowsPerBlock);
 }
 
-__device__ inline f32x16 mfma(u32x4 a, u32x4 b, f32x16 c)
+__device__ inline f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c,
-                                                   0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
-
-// Same-rate f16 variant, used for the cached-key scores: codes are exact in f16 as well, and the
-// rotated, pre-scaled query keeps 11 significant bits instead of 8.
 __device__ inline f32x16 mfma_f16(u32x4 a, u32x4 b, f32x16 c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
@@ -89,7 +106,6 @@ __device__ inline uint32_t pack_f16(float lo, float hi)
     f32x2 f = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
 }
-
 __device__ inline float f16_lo(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[0]; }
 __device__ inline float f16_hi(uint32_t w) { return (float)__builtin_bit_cast(f16x2, w)[1]; }
 
@@ -98,86 +114,98 @@ __device__ inline uint32_t pack_bf16(float lo, float hi)
     f32x2 f = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
+__device__ inline uint16_t bf16_bits(float f) { return (uint16_t)(pack_bf16(f, 0.0f) & 0xffffu); }
+__device__ inline float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// Register j of a packed word: two codes -> two bf16 values OFFSET + code.
-template <int BITS> __device__ inline uint32_t unpack_pair(uint32_t w, int j)
+__device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
 {
-    if (BITS == 2) {
-        const int sh = 5 - 2 * j;
-        const uint32_t x = sh >= 0 ? (w << sh) : (w >> (-sh));
-        return (x & 0x00600060u) | 0x40804080u;
-    } else {
-        const int sh = 3 - 4 * j;
-        const uint32_t x = sh >= 0 ? (w << sh) : (w >> (-sh));
-        return (x & 0x00780078u) | 0x41804180u;
-    }
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
 
-// Key codes become f16 values OFFSET + code: the code sits in the top mantissa bits of 4.0 / 16.0.
-template <int BITS> __device__ inline uint32_t unpack_pair_f16(uint32_t w, int j)
+// (x & mask) | base in one instruction; mask travels in a scalar register, base in a vector register.
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t base)
 {
-    if (BITS == 2) {
-        const int sh = 8 - 2 * j;
-        const uint32_t x = sh >= 0 ? (w << sh) : (w >> (-sh));
-        return (x & 0x03000300u) | 0x44004400u;
-    } else {
-        const int sh = 6 - 4 * j;
-        const uint32_t x = sh >= 0 ? (w << sh) : (w >> (-sh));
-        return (x & 0x03c003c0u) | 0x4c004c00u;
-    }
-}
-
-// A operand (4 registers) of 16-wide slab `slab` of a key tile, from the lane's WPL code words.
-template <int BITS> __device__ inline u32x4 key_operand(const uint32_t *w, int slab)
-{
-    u32x4 r;
-    if (BITS == 2) {
-        const uint32_t word = w[slab >> 1];
-        const int j0 = 4 * (slab & 1);
-        r.x = unpack_pair_f16<2>(word, j0); r.y = unpack_pair_f16<2>(word, j0 + 1);
-        r.z = unpack_pair_f16<2>(word, j0 + 2); r.w = unpack_pair_f16<2>(word, j0 + 3);
-    } else {
-        const uint32_t word = w[slab];
-        r.x = unpack_pair_f16<4>(word, 0); r.y = unpack_pair_f16<4>(word, 1);
-        r.z = unpack_pair_f16<4>(word, 2); r.w = unpack_pair_f16<4>(word, 3);
-    }
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(base));
     return r;
 }
 
-// A operand of a value tile: channel block `blk` (32 channels), token slab `s` (16 tokens).
-template <int BITS> __device__ inline u32x4 value_operand(const uint32_t *w, int blk, int s)
+template <int SH> __device__ inline uint32_t shift(uint32_t w)
+{
+    if constexpr (SH >= 0) return w << SH;
+    else return w >> (-SH);
+}
+
+// Register J of a packed word -> two f16 values OFFSET + code (keys).
+template <int BITS, int J> __device__ inline uint32_t key_pair(uint32_t w)
+{
+    if constexpr (BITS == 2) return and_or(shift<8 - 2 * J>(w), 0x03000300u, 0x44004400u);
+    else return and_or(shift<6 - 4 * J>(w), 0x03c003c0u, 0x4c004c00u);
+}
+// Register J of a packed word -> two bf16 values OFFSET + code (values).
+template <int BITS, int J> __device__ inline uint32_t value_pair(uint32_t w)
+{
+    if constexpr (BITS == 2) return and_or(shift<5 - 2 * J>(w), 0x00600060u, 0x40804080u);
+    else return and_or(shift<3 - 4 * J>(w), 0x00780078u, 0x41804180u);
+}
+
+// A operand of 16-wide slab SLAB of a key tile, from the lane's WPL code words.
+template <int BITS, int SLAB> __device__ inline u32x4 key_operand(const uint32_t *w)
 {
     u32x4 r;
-    if (BITS == 2) {
-        const uint32_t word = w[blk];
-        const int j0 = 4 * s;
-        r.x = unpack_pair<2>(word, j0); r.y = unpack_pair<2>(word, j0 + 1);
-        r.z = unpack_pair<2>(word, j0 + 2); r.w = unpack_pair<2>(word, j0 + 3);
+    if constexpr (BITS == 2) {
+        const uint32_t word = w[SLAB >> 1];
+        constexpr int J0 = 4 * (SLAB & 1);
+        r.x = key_pair<2, J0>(word); r.y = key_pair<2, J0 + 1>(word);
+        r.z = key_pair<2, J0 + 2>(word); r.w = key_pair<2, J0 + 3>(word);
     } else {
-        const uint32_t word = w[2 * blk + s];
-        r.x = unpack_pair<4>(word, 0); r.y = unpack_pair<4>(word, 1);
-        r.z = unpack_pair<4>(word, 2); r.w = unpack_pair<4>(word, 3);
+        const uint32_t word = w[SLAB];
+        r.x = key_pair<4, 0>(word); r.y = key_pair<4, 1>(word);
+        r.z = key_pair<4, 2>(word); r.w = key_pair<4, 3>(word);
+    }
+    return r;
+}
+// A operand of a value tile: channel block BLK (32 channels), token slab S (16 tokens).
+template <int BITS, int BLK, int S> __device__ inline u32x4 value_operand(const uint32_t *w)
+{
+    u32x4 r;
+    if constexpr (BITS == 2) {
+        const uint32_t word = w[BLK];
+        constexpr int J0 = 4 * S;
+        r.x = value_pair<2, J0>(word); r.y = value_pair<2, J0 + 1>(word);
+        r.z = value_pair<2, J0 + 2>(word); r.w = value_pair<2, J0 + 3>(word);
+    } else {
+        const uint32_t word = w[2 * BLK + S];
+        r.x = value_pair<4, 0>(word); r.y = value_pair<4, 1>(word);
+        r.z = value_pair<4, 2>(word); r.w = value_pair<4, 3>(word);
     }
     return r;
 }
 
 __device__ inline float xhalf(float v) { return __shfl_xor(v, 32); }
+// max(v, value held by the same lane of the other half-wave)
+__device__ inline float max_halves(float v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
 
-struct RowState {
-    float m;      // running maximum (log2 domain)
-    float l_s;    // this lane's share of the cached partition sum
-    float l_r;    // this lane's share of the current partition sum
-    float tau;    // this lane's share of sum_i p'_i (OFFSET + z_i)
-};
+template <int I> struct IntC { static constexpr int value = I; };
+template <int N, typename F> __device__ inline void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(IntC<N - 1>{});
+    }
+}
 
 template <int BITS, bool CORR>
 __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
 {
-    constexpr int WPL = Stage<BITS>::WPL;
-    constexpr int kCodeWords = Stage<BITS>::kCodeWords;
+    using St = Stage<BITS>;
+    constexpr int WPL = St::WPL;
     extern __shared__ __align__(16) uint32_t lds[];
-    auto stage_buf = [&](int64_t i) -> uint32_t * { return lds + (i & 1) * Stage<BITS>::kWords; };
-    uint32_t *q_stage = lds + 2 * Stage<BITS>::kWords;
+    uint32_t *q_stage = lds + kBuffers * St::kWords;
     float *row_scal = reinterpret_cast<float *>(q_stage + kRowsPerBlock * kQRowWords);
 
     const CacheView &cv = a.cv;
@@ -204,8 +232,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     const float c_log = a.softmax_scale * kLog2e;
 
     // ---------------------------------------------------------------- query preparation ----
-    // Lane r of the wave rotates query row wave_row0 + r: q~ = Hn q * softmax_scale * log2(e),
-    // rounded to f16; nu = ||q||^2; the row sum of the rounded q~ (needed for the zero-point term).
+    // Lane r of the wave rotates query row wave_row0 + r: q~ = Hn q * softmax_scale * log2(e), split
+    // into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
     uint32_t *my_q = q_stage + (wave * kRowsPerWave) * kQRowWords;
     u32x4 qop[2][8];  // B operands of the score MFMA: lane (n, hh) holds channels 16*slab + 8*hh .. +7 of rows n, n + 32
     {
@@ -238,7 +266,6 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             }
         }
         const float cq = c_log * 0.088388347648318f;
-        // q~ = high + low, both f16: the pair carries ~22 significant bits through the MFMA.
         float ssum = 0.0f;
         uint32_t whi[D / 2], wlo[D / 2];
 #pragma unroll
@@ -250,7 +277,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             ssum += (h0 + f16_lo(wlo[i])) + (h1 + f16_hi(wlo[i]));
         }
         row_scal[2 * (wave * kRowsPerWave + lane)] = ssum;
-        row_scal[2 * (wave * kRowsPerWave + lane) + 1] = -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f);
+        row_scal[2 * (wave * kRowsPerWave + lane) + 1] =
+            CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
         uint32_t *dst = my_q + lane * kQRowWords;
@@ -276,14 +304,30 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         }
     }
     __syncthreads();
-    float ssum[2], nnu[2];
+    // B operand of the constant-term MFMA, per 32-row block.  Lane half 0 multiplies the key's
+    // -(OFFSET + zero) pieces and the mask bias, lane half 1 the key's scale pieces:
+    //   hh = 0: [S_h, S_m, S_l, S_h, S_m, S_l, 1, 0]   S  = sum_c q~_c  in three bf16 pieces
+    //   hh = 1: [N_h, N_l, N_h, N_l, 0, 0, 0, 0]       N  = -nu'        in two bf16 pieces
+    u32x4 rowop[2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        ssum[rb] = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n)];
-        nnu[rb] = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n) + 1];
+        const float ssum = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n)];
+        const float nnu = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n) + 1];
+        const uint16_t s_h = bf16_bits(ssum);
+        const float r1 = ssum - bf16_val(s_h);
+        const uint16_t s_m = bf16_bits(r1);
+        const uint16_t s_l = bf16_bits(r1 - bf16_val(s_m));
+        const uint16_t n_h = bf16_bits(nnu);
+        const uint16_t n_l = bf16_bits(nnu - bf16_val(n_h));
+        const uint32_t one = 0x3f80u;
+        u32x4 w0, w1;
+        w0.x = s_h | ((uint32_t)s_m << 16); w0.y = s_l | ((uint32_t)s_h << 16);
+        w0.z = s_m | ((uint32_t)s_l << 16); w0.w = one;
+        w1.x = n_h | ((uint32_t)n_l << 16); w1.y = w1.x; w1.z = 0u; w1.w = 0u;
+        rowop[rb] = hh ? w1 : w0;
     }
+    const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
 
-    const uint32_t *q_lo = my_q + n * kQRowWords + 4 * hh;
     f32x16 o[4][2];
 #pragma unroll
     for (int b = 0; b < 4; ++b)
@@ -291,191 +335,268 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[b][rb][v] = 0.0f;
-    RowState st[2];
+    float m_ref[2] = {0.0f, 0.0f};      // reference maximum (log2 domain); set by the first tile
+    float l_s[2] = {0.0f, 0.0f}, l_r[2] = {0.0f, 0.0f}, tau[2] = {0.0f, 0.0f};
+    bool first = true;                  // no tile has set the reference yet
+
+    // Leaves the fast loops: move the reference of the rows whose pending tile maximum `tmax` (relative
+    // to the old reference) is too large, and rescale what has been accumulated so far.
+    auto move_reference = [&](float (&e)[2][16], const float (&tmax)[2]) {
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) { st[rb].m = -INFINITY; st[rb].l_s = 0.0f; st[rb].l_r = 0.0f; st[rb].tau = 0.0f; }
+        for (int rb = 0; rb < 2; ++rb) {
+            const bool mv = first || tmax[rb] > kRescaleThreshold;
+            const float delta = mv ? tmax[rb] : 0.0f;
+            const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta);
+            m_ref[rb] += delta;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) e[rb][v] -= delta;
+            l_s[rb] *= alpha;
+            l_r[rb] *= alpha;
+            tau[rb] *= alpha;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[b][rb][v] *= alpha;
+        }
+        first = false;
+    };
 
     // ---------------------------------------------------------------------- cached keys ----
     if (a.cache_len > 0) {
         const int64_t cs = a.cache_start, ce = a.cache_start + a.cache_len;
         const int64_t t_first = cs / kTileTokens, t_last = (ce - 1) / kTileTokens;
-        const int64_t n_stages = (t_last - t_first + kStageTiles) / kStageTiles;
+        const int n_tiles = (int)(t_last - t_first + 1);
+        const int n_stages = (n_tiles + kStageTiles - 1) / kStageTiles;
         const int64_t head_tile0 = (int64_t)head * cv.cap_tiles;
         const int64_t meta0 = head_tile0 * kTileTokens;
+        const int64_t cap_tokens = cv.cap_tiles * kTileTokens;
 
-        // Loader: the stage's K codes, V codes and the four float arrays are contiguous in memory.
-        constexpr int kCodeVecs = kCodeWords / 4;          // 16-byte vectors per tensor per stage
-        constexpr int kCodeIters = kCodeVecs / 256;        // 1 (2 bit) or 2 (4 bit)
+        // ---- loader: global -> registers (prefetch), registers -> LDS (commit, builds the constants)
+        constexpr int kCodeIters = St::kCodeWords / 4 / 256;   // 16-byte vectors per thread and tensor
         u32x4 pre_k[kCodeIters], pre_v[kCodeIters];
-        f32x2 pre_meta;
-        auto prefetch = [&](int64_t stage) {
-            const int64_t tile0 = t_first + stage * kStageTiles;
-            // Never read past the cache storage: clamp the vector's tile, the data is not used then.
+        float pre_a = 0.0f, pre_b = 0.0f, pre_c = 0.0f;
+        bool pre_valid = false;
+        const int ld_key = tid & 127, ld_half = tid >> 7;       // one (key, operand half) per thread
+        auto prefetch = [&](int stage) {
+            if (stage >= n_stages) return;
+            const int64_t tile0 = t_first + (int64_t)stage * kStageTiles;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
                 const int vec = tid + 256 * it;
                 int64_t tile = tile0 + vec / (16 * WPL);
-                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;
+                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // never read past the storage
                 const int64_t word = (head_tile0 + tile) * (64 * WPL) + (vec % (16 * WPL)) * 4;
                 pre_k[it] = *reinterpret_cast<const u32x4 *>(cv.k_codes + word);
                 pre_v[it] = *reinterpret_cast<const u32x4 *>(cv.v_codes + word);
             }
-            const int arr = tid >> 6, pair = tid & 63;     // 4 arrays x 64 pairs of floats
-            int64_t tok = tile0 * kTileTokens + 2 * pair;
-            const int64_t cap = cv.cap_tiles * kTileTokens;
-            tok = tok < cap ? tok : cap - 2;
-            const float *src = arr == 0 ? cv.k_scale : arr == 1 ? cv.k_negzero : arr == 2 ? cv.v_scale : cv.v_zero_off;
-            pre_meta = *reinterpret_cast<const f32x2 *>(src + meta0 + tok);
+            int64_t tok = tile0 * kTileTokens + ld_key;
+            pre_valid = tok >= cs && tok < ce;
+            tok = tok < cap_tokens ? tok : cap_tokens - 1;
+            if (ld_half == 0) {
+                pre_a = cv.k_negzero[meta0 + tok];
+                pre_b = cv.k_scale[meta0 + tok];
+            } else {
+                pre_a = cv.k_scale[meta0 + tok];
+                pre_b = cv.v_scale[meta0 + tok];
+                pre_c = cv.v_zero_off[meta0 + tok];
+            }
         };
-        auto commit = [&](uint32_t *buf) {
+        auto commit = [&](int stage) {
+            if (stage >= n_stages) return;
+            uint32_t *buf = lds + (stage % kBuffers) * St::kWords;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
                 const int vec = tid + 256 * it;
-                *reinterpret_cast<u32x4 *>(buf + 4 * vec) = pre_k[it];
-                *reinterpret_cast<u32x4 *>(buf + kCodeWords + 4 * vec) = pre_v[it];
+                *reinterpret_cast<u32x4 *>(buf + St::kK + 4 * vec) = pre_k[it];
+                *reinterpret_cast<u32x4 *>(buf + St::kV + 4 * vec) = pre_v[it];
             }
-            *reinterpret_cast<f32x2 *>(reinterpret_cast<float *>(buf + 2 * kCodeWords) + 2 * tid) = pre_meta;
+            // Position of this key in the per-lane order of the score tile: [tile][hh][4 g + r].
+            const int tl = ld_key >> 5, r = ld_key & 31;
+            const int slot = tl * 32 + ((r >> 2) & 1) * 16 + 4 * (r >> 3) + (r & 3);
+            u32x4 cop;
+            if (ld_half == 0) {
+                // -(OFFSET + zero) in two bf16 pieces (exact for |.| < 2^16), and the window mask.
+                const float nz = pre_valid ? pre_a : 0.0f;
+                const uint16_t z_h = bf16_bits(nz);
+                const uint16_t z_l = bf16_bits(nz - bf16_val(z_h));
+                cop.x = z_h | ((uint32_t)z_h << 16); cop.y = z_h | ((uint32_t)z_l << 16);
+                cop.z = z_l | ((uint32_t)z_l << 16);
+                cop.w = pre_valid ? 0u : (uint32_t)bf16_bits(kMaskBias);
+                reinterpret_cast<float *>(buf + St::kKScale)[slot] = pre_valid ? pre_b : 1.0f;
+            } else {
+                const float ks = pre_valid ? pre_a : 0.0f;
+                const uint16_t k_h = bf16_bits(ks);
+                const uint16_t k_l = bf16_bits(ks - bf16_val(k_h));
+                cop.x = k_h | ((uint32_t)k_h << 16); cop.y = k_l | ((uint32_t)k_l << 16);
+                cop.z = 0u; cop.w = 0u;
+                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_b;
+                const uint16_t v_h = bf16_bits(pre_c);
+                const uint16_t v_l = bf16_bits(pre_c - bf16_val(v_h));
+                reinterpret_cast<uint16_t *>(buf + St::kVzHi)[slot] = v_h;
+                reinterpret_cast<uint16_t *>(buf + St::kVzLo)[slot] = v_l;
+            }
+            *reinterpret_cast<u32x4 *>(buf + St::kCop + (tl * 64 + ld_half * 32 + r) * 4) = cop;
+        };
+
+        // ---- pieces of one pipeline iteration
+        // Scores of tile t (raw accumulators): constant-term MFMA, then high and low query parts.
+        auto score_tile = [&](int t, f32x16 (&sn)[2]) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const int tl = t & 3;
+            uint32_t kw[WPL];
+            {
+                const uint32_t *src = buf + St::kK + tl * 64 * WPL + lane * WPL;
+#pragma unroll
+                for (int i = 0; i < WPL / 4; ++i) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                    kw[4 * i] = w.x; kw[4 * i + 1] = w.y; kw[4 * i + 2] = w.z; kw[4 * i + 3] = w.w;
+                }
+            }
+            const u32x4 cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
+            f32x16 zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+            sn[0] = mfma_bf16(cop, rowop[0], zero);
+            sn[1] = mfma_bf16(cop, rowop[1], zero);
+            // The low parts of q~ stay in LDS: the offset is made opaque so that the loads are issued per
+            // tile instead of being hoisted into registers that do not exist.
+            uint32_t off = lo_off;
+            asm volatile("" : "+v"(off));
+            const uint32_t *qlo = q_stage + off;
+            static_for<8>([&](auto s_) {
+                constexpr int SLAB = decltype(s_)::value;
+                const u32x4 kop = key_operand<BITS, SLAB>(kw);
+                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(qlo + 8 * SLAB);
+                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * SLAB);
+                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
+                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
+                sn[0] = mfma_f16(kop, lo0, sn[0]);
+                sn[1] = mfma_f16(kop, lo1, sn[1]);
+            });
+        };
+        // e = scale_i * raw - reference; returns the tile maximum of e per row block.
+        auto finalize_tile = [&](int t, const f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2]) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const float *ks = reinterpret_cast<const float *>(buf + St::kKScale) + (t & 3) * 32 + hh * 16;
+            float k_scale[16];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 c = *reinterpret_cast<const float4 *>(ks + 4 * g);
+                k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
+            }
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(k_scale[v], sn[rb][v], -m_ref[rb]);
+                float mx = fmaxf(e[rb][0], e[rb][1]);
+#pragma unroll
+                for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(e[rb][v], e[rb][v + 1]));
+                tmax[rb] = max_halves(mx);
+            }
+        };
+        // p = 2^e, partial sums, p' = p * value-scale rounded to bf16 (B operands), tau.
+        auto exp_tile = [&](int t, const float (&e)[2][16], u32x4 (&pop)[2][2]) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const int pos = (t & 3) * 32 + hh * 16;
+            const float *vsp = reinterpret_cast<const float *>(buf + St::kVScale) + pos;
+            float v_scale[16];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 c = *reinterpret_cast<const float4 *>(vsp + 4 * g);
+                v_scale[4 * g] = c.x; v_scale[4 * g + 1] = c.y; v_scale[4 * g + 2] = c.z; v_scale[4 * g + 3] = c.w;
+            }
+            uint32_t zh[8], zl[8];
+            {
+                const u32x4 h0 = *reinterpret_cast<const u32x4 *>(buf + St::kVzHi + pos / 2);
+                const u32x4 h1 = *reinterpret_cast<const u32x4 *>(buf + St::kVzHi + pos / 2 + 4);
+                const u32x4 l0 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2);
+                const u32x4 l1 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2 + 4);
+                zh[0] = h0.x; zh[1] = h0.y; zh[2] = h0.z; zh[3] = h0.w; zh[4] = h1.x; zh[5] = h1.y; zh[6] = h1.z; zh[7] = h1.w;
+                zl[0] = l0.x; zl[1] = l0.y; zl[2] = l0.z; zl[3] = l0.w; zl[4] = l1.x; zl[5] = l1.y; zl[6] = l1.z; zl[7] = l1.w;
+            }
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                float lsum = 0.0f, tacc = 0.0f;
+                uint32_t pw[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float p0 = __builtin_amdgcn_exp2f(e[rb][2 * i]);
+                    const float p1 = __builtin_amdgcn_exp2f(e[rb][2 * i + 1]);
+                    lsum += p0 + p1;
+                    pw[i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
+                    tacc = dot2_bf16(pw[i], zh[i], tacc);
+                    tacc = dot2_bf16(pw[i], zl[i], tacc);
+                }
+                l_s[rb] += lsum;
+                tau[rb] += tacc;
+                pop[rb][0].x = pw[0]; pop[rb][0].y = pw[1]; pop[rb][0].z = pw[2]; pop[rb][0].w = pw[3];
+                pop[rb][1].x = pw[4]; pop[rb][1].y = pw[5]; pop[rb][1].z = pw[6]; pop[rb][1].w = pw[7];
+            }
+        };
+        // O^T += V^T P^T on raw codes.
+        auto pv_tile = [&](int t, const u32x4 (&pop)[2][2]) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            uint32_t vw[WPL];
+            {
+                const uint32_t *src = buf + St::kV + (t & 3) * 64 * WPL + lane * WPL;
+#pragma unroll
+                for (int i = 0; i < WPL / 4; ++i) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                    vw[4 * i] = w.x; vw[4 * i + 1] = w.y; vw[4 * i + 2] = w.z; vw[4 * i + 3] = w.w;
+                }
+            }
+            static_for<4>([&](auto b_) {
+                constexpr int B = decltype(b_)::value;
+                const u32x4 v0 = value_operand<BITS, B, 0>(vw);
+                const u32x4 v1 = value_operand<BITS, B, 1>(vw);
+                o[B][0] = mfma_bf16(v0, pop[0][0], o[B][0]);
+                o[B][1] = mfma_bf16(v0, pop[1][0], o[B][1]);
+                o[B][0] = mfma_bf16(v1, pop[0][1], o[B][0]);
+                o[B][1] = mfma_bf16(v1, pop[1][1], o[B][1]);
+            });
+        };
+        // A stage becomes visible one tile before its first tile is scored.
+        auto open_stage = [&](int stage) {
+            commit(stage);
+            prefetch(stage + 1);
+            __syncthreads();
         };
 
         prefetch(0);
-        commit(stage_buf(0));
-        __syncthreads();
-        for (int64_t stage = 0; stage < n_stages; ++stage) {
-            const bool more = stage + 1 < n_stages;
-            if (more) prefetch(stage + 1);
-            const uint32_t *buf = stage_buf(stage);
-            const float *meta = reinterpret_cast<const float *>(buf + 2 * kCodeWords);
-            const int64_t tile0 = t_first + stage * kStageTiles;
-            const int tiles_here = (int)((t_last - tile0 + 1) < kStageTiles ? (t_last - tile0 + 1) : kStageTiles);
-            for (int tl = 0; tl < tiles_here; ++tl) {
-                const int64_t tile = tile0 + tl;
-                // ---- scores: S^T = K q~^T on raw codes
-                uint32_t kw[WPL];
-                {
-                    const uint32_t *src = buf + tl * 64 * WPL + lane * WPL;
-#pragma unroll
-                    for (int i = 0; i < WPL / 4; ++i) {
-                        const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
-                        kw[4 * i] = w.x; kw[4 * i + 1] = w.y; kw[4 * i + 2] = w.z; kw[4 * i + 3] = w.w;
-                    }
+        open_stage(0);
+        f32x16 sn[2];
+        float e[2][16], tmax[2];
+        u32x4 pop[2][2];
+        score_tile(0, sn);
+        finalize_tile(0, sn, e, tmax);
+        int t = 0;
+        bool done = false;
+        while (!done) {
+            move_reference(e, tmax);
+            // fast loop: nothing in here touches the accumulators except the MFMAs
+            for (;;) {
+                if (t + 1 >= n_tiles) {
+                    exp_tile(t, e, pop);
+                    pv_tile(t, pop);
+                    done = true;
+                    break;
                 }
-                f32x16 s[2];
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s[rb][v] = 0.0f;
-                // Opaque copy of the address so the loads below are issued per tile instead of being
-                // hoisted out of the loop into registers that do not exist.
-                const uint32_t *q_lo_t = q_lo;
-                asm volatile("" : "+v"(q_lo_t));
-#pragma unroll
-                for (int slab = 0; slab < 8; ++slab) {
-                    const u32x4 kop = key_operand<BITS>(kw, slab);
-                    s[0] = mfma_f16(kop, qop[0][slab], s[0]);
-                    s[1] = mfma_f16(kop, qop[1][slab], s[1]);
-                    // low parts of q~ stay in LDS (the register file is full): 2 x 16 bytes per slab
-                    const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(q_lo_t + 8 * slab);
-                    const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(q_lo_t + 32 * kQRowWords + 8 * slab);
-                    s[0] = mfma_f16(kop, lo0, s[0]);
-                    s[1] = mfma_f16(kop, lo1, s[1]);
-                }
-                // ---- per-key constants of the 16 keys this lane sees: keys 8g + 4hh + 0..3, g = 0..3
-                float k_scale[16], k_nz[16], v_scale[16], v_zo[16];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int key = tl * kTileTokens + 8 * g + 4 * hh;
-                    const float4 c0 = *reinterpret_cast<const float4 *>(meta + key);
-                    const float4 c1 = *reinterpret_cast<const float4 *>(meta + kStageKeys + key);
-                    const float4 c2 = *reinterpret_cast<const float4 *>(meta + 2 * kStageKeys + key);
-                    const float4 c3 = *reinterpret_cast<const float4 *>(meta + 3 * kStageKeys + key);
-                    k_scale[4 * g] = c0.x; k_scale[4 * g + 1] = c0.y; k_scale[4 * g + 2] = c0.z; k_scale[4 * g + 3] = c0.w;
-                    k_nz[4 * g] = c1.x; k_nz[4 * g + 1] = c1.y; k_nz[4 * g + 2] = c1.z; k_nz[4 * g + 3] = c1.w;
-                    v_scale[4 * g] = c2.x; v_scale[4 * g + 1] = c2.y; v_scale[4 * g + 2] = c2.z; v_scale[4 * g + 3] = c2.w;
-                    v_zo[4 * g] = c3.x; v_zo[4 * g + 1] = c3.y; v_zo[4 * g + 2] = c3.z; v_zo[4 * g + 3] = c3.w;
-                }
-                const int64_t key_base = tile * kTileTokens + 4 * hh;
-                const bool edge = key_base - 4 * hh < cs || key_base - 4 * hh + kTileTokens > ce;
-                // ---- softmax on the two 32-row blocks
-                u32x4 pop[2][2];
-#pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
-                    float t[16];
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float x = fmaf(k_nz[v], ssum[rb], s[rb][v]);
-                        if (CORR) x = fmaf(k_scale[v], nnu[rb], x);
-                        t[v] = k_scale[v] * x;
-                    }
-                    if (edge) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int64_t key = key_base + 8 * (v >> 2) + (v & 3);
-                            t[v] = (key >= cs && key < ce) ? t[v] : -INFINITY;
-                        }
-                    }
-                    float tmax = t[0];
-#pragma unroll
-                    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, t[v]);
-                    tmax = fmaxf(tmax, xhalf(tmax));
-                    const float m_new = fmaxf(st[rb].m, tmax);
-                    const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-                    if (__any(m_new > st[rb].m)) {
-                        const float alpha = __builtin_amdgcn_exp2f(st[rb].m - m_use);
-                        st[rb].l_s *= alpha;
-                        st[rb].tau *= alpha;
-#pragma unroll
-                        for (int b = 0; b < 4; ++b)
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) o[b][rb][v] *= alpha;
-                        st[rb].m = m_new;
-                    }
-                    float lsum = 0.0f, tau = 0.0f;
-                    uint32_t pw[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float p0 = __builtin_amdgcn_exp2f(t[2 * i] - m_use);
-                        const float p1 = __builtin_amdgcn_exp2f(t[2 * i + 1] - m_use);
-                        lsum += p0 + p1;
-                        pw[i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
-                        tau = fmaf(__uint_as_float(pw[i] << 16), v_zo[2 * i], tau);
-                        tau = fmaf(__uint_as_float(pw[i] & 0xffff0000u), v_zo[2 * i + 1], tau);
-                    }
-                    st[rb].l_s += lsum;
-                    st[rb].tau += tau;
-                    pop[rb][0].x = pw[0]; pop[rb][0].y = pw[1]; pop[rb][0].z = pw[2]; pop[rb][0].w = pw[3];
-                    pop[rb][1].x = pw[4]; pop[rb][1].y = pw[5]; pop[rb][1].z = pw[6]; pop[rb][1].w = pw[7];
-                }
-                // ---- O^T += V^T P^T on raw codes
-                uint32_t vw[WPL];
-                {
-                    const uint32_t *src = buf + kCodeWords + tl * 64 * WPL + lane * WPL;
-#pragma unroll
-                    for (int i = 0; i < WPL / 4; ++i) {
-                        const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
-                        vw[4 * i] = w.x; vw[4 * i + 1] = w.y; vw[4 * i + 2] = w.z; vw[4 * i + 3] = w.w;
-                    }
-                }
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-#pragma unroll
-                    for (int sl = 0; sl < 2; ++sl) {
-                        const u32x4 vop = value_operand<BITS>(vw, b, sl);
-                        o[b][0] = mfma(vop, pop[0][sl], o[b][0]);
-                        o[b][1] = mfma(vop, pop[1][sl], o[b][1]);
-                    }
-                }
+                if (((t + 1) & 3) == 0) open_stage((t + 1) >> 2);
+                score_tile(t + 1, sn);
+                exp_tile(t, e, pop);
+                pv_tile(t, pop);
+                finalize_tile(t + 1, sn, e, tmax);
+                ++t;
+                if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
             }
-            if (more) commit(stage_buf(stage + 1));
-            __syncthreads();
         }
 
         // ---- leave the rotated basis: O <- Hn^T (O_rot - tau 1).  Channel index of register
         // (b, v) in lane half hh: c = 32 b + 8 (v >> 2) + 4 hh + (v & 3).
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            // bits 0, 1 (v bits 0, 1) and bits 3, 4 (v bits 2, 3)
 #pragma unroll
-            for (int h = 1; h < 16; h <<= 1) {
+            for (int h = 1; h < 16; h <<= 1) {   // channel bits 0, 1 (v bits 0, 1) and 3, 4 (v bits 2, 3)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -486,9 +607,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                             o[b][rb][v + h] = p - q2;
                         }
             }
-            // bits 5, 6 (channel block)
 #pragma unroll
-            for (int h = 1; h < 4; h <<= 1) {
+            for (int h = 1; h < 4; h <<= 1) {    // channel bits 5, 6 (block)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     if ((b & h) == 0) {
@@ -500,16 +620,15 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                         }
                     }
             }
-            // bit 2 lives in the lane half
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+            for (int b = 0; b < 4; ++b)          // channel bit 2 lives in the lane half
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float own = o[b][rb][v], other = xhalf(own);
                     o[b][rb][v] = (hh ? other - own : own + other) * 0.088388347648318f;
                 }
             // Hn^T (tau 1) = tau sqrt(d) e_0: only channel 0 (lane half 0, block 0, register 0) sees it.
-            const float tau_all = st[rb].tau + xhalf(st[rb].tau);
+            const float tau_all = tau[rb] + xhalf(tau[rb]);
             if (hh == 0) o[0][rb][0] -= tau_all * 11.313708498984761f;
         }
     }
@@ -529,12 +648,12 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         }
         // V^T staging: two buffers of 128 channel rows x 32 tokens (bf16), reusing the query staging area.
         __syncthreads();
-        auto vt = [&](int64_t i) -> uint16_t * { return reinterpret_cast<uint16_t *>(q_stage + (i & 1) * D * kVtRowWords); };
-        const int64_t n_tiles = (a.n_cur + kTileTokens - 1) / kTileTokens;
+        auto vt = [&](int i) -> uint16_t * { return reinterpret_cast<uint16_t *>(q_stage + (i & 1) * D * kVtRowWords); };
+        const int n_tiles = (int)((a.n_cur + kTileTokens - 1) / kTileTokens);
         u32x4 pre_vt[2];
         const int ld_key = tid & 31, ld_oct = tid >> 5;  // octets ld_oct and ld_oct + 8
-        auto prefetch_v = [&](int64_t tile) {
-            int64_t key = tile * kTileTokens + ld_key;
+        auto prefetch_v = [&](int tile) {
+            int64_t key = (int64_t)tile * kTileTokens + ld_key;
             key = key < a.n_cur ? key : a.n_cur - 1;
             const uint16_t *src = v_base + key * a.stride_token;
             pre_vt[0] = *reinterpret_cast<const u32x4 *>(src + 8 * ld_oct);
@@ -545,83 +664,67 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             for (int it = 0; it < 2; ++it) {
                 const uint32_t ws[4] = {pre_vt[it].x, pre_vt[it].y, pre_vt[it].z, pre_vt[it].w};
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int ch = 8 * (ld_oct + 8 * it) + e;
-                    const uint16_t val = (uint16_t)(e & 1 ? ws[e >> 1] >> 16 : ws[e >> 1] & 0xffffu);
+                for (int el = 0; el < 8; ++el) {
+                    const int ch = 8 * (ld_oct + 8 * it) + el;
+                    const uint16_t val = (uint16_t)(el & 1 ? ws[el >> 1] >> 16 : ws[el >> 1] & 0xffffu);
                     buf[ch * (2 * kVtRowWords) + ld_key] = val;
                 }
             }
         };
-        prefetch_v(0);
-        commit_v(vt(0));
-        __syncthreads();
-        for (int64_t tile = 0; tile < n_tiles; ++tile) {
-            const bool more = tile + 1 < n_tiles;
-            if (more) prefetch_v(tile + 1);
-            // ---- scores S^T = K q^T, K rows straight from memory
+        auto score_cur = [&](int tile, float (&e)[2][16], float (&tmax)[2]) {
             f32x16 s[2];
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[rb][v] = 0.0f;
-            {
-                int64_t key = tile * kTileTokens + n;
-                key = key < a.n_cur ? key : a.n_cur - 1;
-                const uint16_t *src = k_base + key * a.stride_token + 8 * hh;
-                u32x4 kop[8];
+            int64_t key = (int64_t)tile * kTileTokens + n;
+            key = key < a.n_cur ? key : a.n_cur - 1;
+            const uint16_t *src = k_base + key * a.stride_token + 8 * hh;
+            u32x4 kop[8];
 #pragma unroll
-                for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 16 * slab);
+            for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 16 * slab);
 #pragma unroll
-                for (int slab = 0; slab < 8; ++slab) {
-                    s[0] = mfma(kop[slab], qop[0][slab], s[0]);
-                    s[1] = mfma(kop[slab], qop[1][slab], s[1]);
-                }
+            for (int slab = 0; slab < 8; ++slab) {
+                s[0] = mfma_bf16(kop[slab], qop[0][slab], s[0]);
+                s[1] = mfma_bf16(kop[slab], qop[1][slab], s[1]);
             }
-            const int64_t key_base = tile * kTileTokens + 4 * hh;
-            const bool edge = (tile + 1) * kTileTokens > a.n_cur;
-            u32x4 pop[2][2];
+            const int64_t key_base = (int64_t)tile * kTileTokens + 4 * hh;
+            const bool edge = (int64_t)(tile + 1) * kTileTokens > a.n_cur;
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
-                float t[16];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) t[v] = s[rb][v] * c_log;
+                for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(s[rb][v], c_log, -m_ref[rb]);
                 if (edge) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int64_t key = key_base + 8 * (v >> 2) + (v & 3);
-                        t[v] = key < a.n_cur ? t[v] : -INFINITY;
+                        const int64_t kk = key_base + 8 * (v >> 2) + (v & 3);
+                        e[rb][v] = kk < a.n_cur ? e[rb][v] : kMaskBias;
                     }
                 }
-                float tmax = t[0];
+                float mx = fmaxf(e[rb][0], e[rb][1]);
 #pragma unroll
-                for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, t[v]);
-                tmax = fmaxf(tmax, xhalf(tmax));
-                const float m_new = fmaxf(st[rb].m, tmax);
-                const float m_use = m_new == -INFINITY ? 0.0f : m_new;
-                if (__any(m_new > st[rb].m)) {
-                    const float alpha = __builtin_amdgcn_exp2f(st[rb].m - m_use);
-                    st[rb].l_s *= alpha;
-                    st[rb].l_r *= alpha;
+                for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(e[rb][v], e[rb][v + 1]));
+                tmax[rb] = max_halves(mx);
+            }
+        };
+        auto pv_cur = [&](int tile, const float (&e)[2][16]) {
+            u32x4 pop[2][2];
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) o[b][rb][v] *= alpha;
-                    st[rb].m = m_new;
-                }
+            for (int rb = 0; rb < 2; ++rb) {
                 float lsum = 0.0f;
                 uint32_t pw[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float p0 = __builtin_amdgcn_exp2f(t[2 * i] - m_use);
-                    const float p1 = __builtin_amdgcn_exp2f(t[2 * i + 1] - m_use);
+                    const float p0 = __builtin_amdgcn_exp2f(e[rb][2 * i]);
+                    const float p1 = __builtin_amdgcn_exp2f(e[rb][2 * i + 1]);
                     lsum += p0 + p1;
                     pw[i] = pack_bf16(p0, p1);
                 }
-                st[rb].l_r += lsum;
+                l_r[rb] += lsum;
                 pop[rb][0].x = pw[0]; pop[rb][0].y = pw[1]; pop[rb][0].z = pw[2]; pop[rb][0].w = pw[3];
                 pop[rb][1].x = pw[4]; pop[rb][1].y = pw[5]; pop[rb][1].z = pw[6]; pop[rb][1].w = pw[7];
             }
-            // ---- O^T += V^T P^T, V^T from LDS: tokens 16 sl + 4 hh + 0..3 and 16 sl + 8 + 4 hh + 0..3
+            // V^T from LDS: tokens 16 sl + 4 hh + 0..3 and 16 sl + 8 + 4 hh + 0..3
             const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(vt(tile));
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -632,12 +735,32 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     const u32x2 hi = *reinterpret_cast<const u32x2 *>(rowp + 8 * sl + 4);
                     u32x4 vop;
                     vop.x = lo.x; vop.y = lo.y; vop.z = hi.x; vop.w = hi.y;
-                    o[b][0] = mfma(vop, pop[0][sl], o[b][0]);
-                    o[b][1] = mfma(vop, pop[1][sl], o[b][1]);
+                    o[b][0] = mfma_bf16(vop, pop[0][sl], o[b][0]);
+                    o[b][1] = mfma_bf16(vop, pop[1][sl], o[b][1]);
                 }
             }
-            if (more) commit_v(vt(tile + 1));
-            __syncthreads();
+        };
+
+        prefetch_v(0);
+        commit_v(vt(0));
+        __syncthreads();
+        float e[2][16], tmax[2];
+        int tile = 0;
+        score_cur(0, e, tmax);
+        bool done = false;
+        while (!done) {
+            move_reference(e, tmax);
+            for (;;) {
+                const bool more = tile + 1 < n_tiles;
+                if (more) prefetch_v(tile + 1);
+                pv_cur(tile, e);
+                if (more) commit_v(vt(tile + 1));
+                __syncthreads();
+                if (!more) { done = true; break; }
+                ++tile;
+                score_cur(tile, e, tmax);
+                if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
+            }
         }
     }
 
@@ -645,9 +768,9 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     uint16_t *out_base = static_cast<uint16_t *>(a.out) + head_off;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
-        const float l_s = st[rb].l_s + xhalf(st[rb].l_s);
-        const float l_r = st[rb].l_r + xhalf(st[rb].l_r);
-        const float inv = 1.0f / (l_s + l_r);
+        const float ls = l_s[rb] + xhalf(l_s[rb]);
+        const float lr = l_r[rb] + xhalf(l_r[rb]);
+        const float inv = 1.0f / (ls + lr);
         const int64_t row = wave_row0 + 32 * rb + n;
         if (row < a.m) {
             uint16_t *dst = out_base + row * a.stride_token + 4 * hh;
@@ -660,7 +783,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     w.y = pack_bf16(o[b][rb][4 * g + 2] * inv, o[b][rb][4 * g + 3] * inv);
                     *reinterpret_cast<u32x2 *>(dst + 32 * b + 8 * g) = w;
                 }
-            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = l_s * inv;
+            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = ls * inv;
         }
     }
 }
@@ -687,6 +810,7 @@ template <int BITS, bool CORR> hipError_t launch(const AttentionArgs &a, hipStre
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream)
 {
     if (a.cv.head_dim != D || a.cv.io_dtype != KVQ_BF16) return hipErrorInvalidValue;
+    if (a.cache_len > (int64_t)0x3fffffff * kTileTokens) return hipErrorInvalidValue;
     if (a.cv.bits == 2) return a.correction ? launch<2, true>(a, stream) : launch<2, false>(a, stream);
     if (a.cv.bits == 4) return a.correction ? launch<4, true>(a, stream) : launch<4, false>(a, stream);
     return hipErrorInvalidValue;

@@ -122,12 +122,23 @@ __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
 
-// (x & mask) | base in one instruction; mask travels in a scalar register, base in a vector register.
-__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t base)
+// Unpack constants.  They are passed through an empty asm once per kernel so that the compiler
+// keeps them in registers (mask in a scalar, base in a vector register) and selects v_and_or_b32
+// for (x & mask) | base; the instruction itself is emitted by the compiler, which matters because
+// it must know about the vector write in front of the matrix instruction that reads the register.
+struct UnpackConsts {
+    uint32_t kmask, kbase, vmask, vbase;
+};
+template <int BITS> __device__ inline UnpackConsts make_unpack_consts()
 {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(base));
-    return r;
+    UnpackConsts c;
+    c.kmask = BITS == 2 ? 0x03000300u : 0x03c003c0u;
+    c.kbase = BITS == 2 ? 0x44004400u : 0x4c004c00u;
+    c.vmask = BITS == 2 ? 0x00600060u : 0x00780078u;
+    c.vbase = BITS == 2 ? 0x40804080u : 0x41804180u;
+    asm volatile("" : "+s"(c.kmask), "+s"(c.vmask));
+    asm volatile("" : "+v"(c.kbase), "+v"(c.vbase));
+    return c;
 }
 
 template <int SH> __device__ inline uint32_t shift(uint32_t w)
@@ -137,47 +148,47 @@ template <int SH> __device__ inline uint32_t shift(uint32_t w)
 }
 
 // Register J of a packed word -> two f16 values OFFSET + code (keys).
-template <int BITS, int J> __device__ inline uint32_t key_pair(uint32_t w)
+template <int BITS, int J> __device__ inline uint32_t key_pair(uint32_t w, const UnpackConsts &c)
 {
-    if constexpr (BITS == 2) return and_or(shift<8 - 2 * J>(w), 0x03000300u, 0x44004400u);
-    else return and_or(shift<6 - 4 * J>(w), 0x03c003c0u, 0x4c004c00u);
+    if constexpr (BITS == 2) return (shift<8 - 2 * J>(w) & c.kmask) | c.kbase;
+    else return (shift<6 - 4 * J>(w) & c.kmask) | c.kbase;
 }
 // Register J of a packed word -> two bf16 values OFFSET + code (values).
-template <int BITS, int J> __device__ inline uint32_t value_pair(uint32_t w)
+template <int BITS, int J> __device__ inline uint32_t value_pair(uint32_t w, const UnpackConsts &c)
 {
-    if constexpr (BITS == 2) return and_or(shift<5 - 2 * J>(w), 0x00600060u, 0x40804080u);
-    else return and_or(shift<3 - 4 * J>(w), 0x00780078u, 0x41804180u);
+    if constexpr (BITS == 2) return (shift<5 - 2 * J>(w) & c.vmask) | c.vbase;
+    else return (shift<3 - 4 * J>(w) & c.vmask) | c.vbase;
 }
 
 // A operand of 16-wide slab SLAB of a key tile, from the lane's WPL code words.
-template <int BITS, int SLAB> __device__ inline u32x4 key_operand(const uint32_t *w)
+template <int BITS, int SLAB> __device__ inline u32x4 key_operand(const uint32_t *w, const UnpackConsts &c)
 {
     u32x4 r;
     if constexpr (BITS == 2) {
         const uint32_t word = w[SLAB >> 1];
         constexpr int J0 = 4 * (SLAB & 1);
-        r.x = key_pair<2, J0>(word); r.y = key_pair<2, J0 + 1>(word);
-        r.z = key_pair<2, J0 + 2>(word); r.w = key_pair<2, J0 + 3>(word);
+        r.x = key_pair<2, J0>(word, c); r.y = key_pair<2, J0 + 1>(word, c);
+        r.z = key_pair<2, J0 + 2>(word, c); r.w = key_pair<2, J0 + 3>(word, c);
     } else {
         const uint32_t word = w[SLAB];
-        r.x = key_pair<4, 0>(word); r.y = key_pair<4, 1>(word);
-        r.z = key_pair<4, 2>(word); r.w = key_pair<4, 3>(word);
+        r.x = key_pair<4, 0>(word, c); r.y = key_pair<4, 1>(word, c);
+        r.z = key_pair<4, 2>(word, c); r.w = key_pair<4, 3>(word, c);
     }
     return r;
 }
 // A operand of a value tile: channel block BLK (32 channels), token slab S (16 tokens).
-template <int BITS, int BLK, int S> __device__ inline u32x4 value_operand(const uint32_t *w)
+template <int BITS, int BLK, int S> __device__ inline u32x4 value_operand(const uint32_t *w, const UnpackConsts &c)
 {
     u32x4 r;
     if constexpr (BITS == 2) {
         const uint32_t word = w[BLK];
         constexpr int J0 = 4 * S;
-        r.x = value_pair<2, J0>(word); r.y = value_pair<2, J0 + 1>(word);
-        r.z = value_pair<2, J0 + 2>(word); r.w = value_pair<2, J0 + 3>(word);
+        r.x = value_pair<2, J0>(word, c); r.y = value_pair<2, J0 + 1>(word, c);
+        r.z = value_pair<2, J0 + 2>(word, c); r.w = value_pair<2, J0 + 3>(word, c);
     } else {
         const uint32_t word = w[2 * BLK + S];
-        r.x = value_pair<4, 0>(word); r.y = value_pair<4, 1>(word);
-        r.z = value_pair<4, 2>(word); r.w = value_pair<4, 3>(word);
+        r.x = value_pair<4, 0>(word, c); r.y = value_pair<4, 1>(word, c);
+        r.z = value_pair<4, 2>(word, c); r.w = value_pair<4, 3>(word, c);
     }
     return r;
 }
@@ -230,6 +241,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     const int64_t head_off = (int64_t)head * a.stride_head;
     const uint16_t *q_base = static_cast<const uint16_t *>(a.q) + head_off;
     const float c_log = a.softmax_scale * kLog2e;
+    const UnpackConsts uc = make_unpack_consts<BITS>();
 
     // ---------------------------------------------------------------- query preparation ----
     // Lane r of the wave rotates query row wave_row0 + r: q~ = Hn q * softmax_scale * log2(e), split
@@ -335,6 +347,14 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[b][rb][v] = 0.0f;
+    // Keeps the 128 output accumulators in accumulation registers at the points where the fast loops
+    // are entered, so that the loops carry them there instead of copying them around.
+    auto pin_accumulators = [&]() {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) asm volatile("" : "+a"(o[b][rb]));
+    };
     float m_ref[2] = {0.0f, 0.0f};      // reference maximum (log2 domain); set by the first tile
     float l_s[2] = {0.0f, 0.0f}, l_r[2] = {0.0f, 0.0f}, tau[2] = {0.0f, 0.0f};
     bool first = true;                  // no tile has set the reference yet
@@ -359,6 +379,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 for (int v = 0; v < 16; ++v) o[b][rb][v] *= alpha;
         }
         first = false;
+        pin_accumulators();
     };
 
     // ---------------------------------------------------------------------- cached keys ----
@@ -465,7 +486,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             const uint32_t *qlo = q_stage + off;
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
-                const u32x4 kop = key_operand<BITS, SLAB>(kw);
+                const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
                 const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(qlo + 8 * SLAB);
                 const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * SLAB);
                 sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
@@ -547,8 +568,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             }
             static_for<4>([&](auto b_) {
                 constexpr int B = decltype(b_)::value;
-                const u32x4 v0 = value_operand<BITS, B, 0>(vw);
-                const u32x4 v1 = value_operand<BITS, B, 1>(vw);
+                const u32x4 v0 = value_operand<BITS, B, 0>(vw, uc);
+                const u32x4 v1 = value_operand<BITS, B, 1>(vw, uc);
                 o[B][0] = mfma_bf16(v0, pop[0][0], o[B][0]);
                 o[B][1] = mfma_bf16(v0, pop[1][0], o[B][1]);
                 o[B][0] = mfma_bf16(v1, pop[0][1], o[B][0]);
@@ -783,7 +804,11 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     w.y = pack_bf16(o[b][rb][4 * g + 2] * inv, o[b][rb][4 * g + 3] * inv);
                     *reinterpret_cast<u32x2 *>(dst + 32 * b + 8 * g) = w;
                 }
+#ifdef KVQ_DEBUG_DUMP
+            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = KVQ_DEBUG_DUMP == 1 ? m_ref[rb] : KVQ_DEBUG_DUMP == 2 ? ls : KVQ_DEBUG_DUMP == 3 ? tau[rb] : lr;
+#else
             if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = ls * inv;
+#endif
         }
     }
 }

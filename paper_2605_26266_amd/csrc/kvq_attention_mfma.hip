@@ -59,6 +59,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+#ifndef KVQ_CHUNK_FENCE
+#define KVQ_CHUNK_FENCE() __builtin_amdgcn_sched_barrier(0)
+#endif
+
 constexpr int D = 128;
 constexpr int kWaves = 4;
 constexpr int kRowsPerWave = 64;
@@ -339,6 +343,12 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         rowop[rb] = hh ? w1 : w0;
     }
     const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
+    // The 64 registers of query operands live in accumulation registers (MFMA reads them from there
+    // directly), which leaves the vector registers to the score tile in flight.
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
 
     f32x16 o[4][2];
 #pragma unroll
@@ -576,6 +586,118 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 o[B][1] = mfma_bf16(v1, pop[1][1], o[B][1]);
             });
         };
+        // One steady-state iteration, interleaved by hand: the score MFMAs of tile t+1 (4 per key slab)
+        // next to one eighth of the exponential work of tile t, then the P*V MFMAs of tile t (4 per channel
+        // block) next to one quarter of the score scaling of tile t+1.  Nothing crosses a chunk boundary,
+        // so every group of four 32-cycle MFMAs has about as much independent vector work beside it.
+        auto fused_iteration = [&](int t, f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2], u32x4 (&pop)[2][2]) {
+            const uint32_t *bufn = lds + (((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
+            const uint32_t *bufc = lds + ((t >> 2) % kBuffers) * St::kWords;         // holds tile t
+            const int tln = (t + 1) & 3, tlc = t & 3;
+            uint32_t kw[WPL];
+            {
+                const uint32_t *src = bufn + St::kK + tln * 64 * WPL + lane * WPL;
+#pragma unroll
+                for (int i = 0; i < WPL / 4; ++i) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                    kw[4 * i] = w.x; kw[4 * i + 1] = w.y; kw[4 * i + 2] = w.z; kw[4 * i + 3] = w.w;
+                }
+            }
+            const u32x4 cop = *reinterpret_cast<const u32x4 *>(bufn + St::kCop + (tln * 64 + lane) * 4);
+            const int pos = tlc * 32 + hh * 16;
+            float v_scale[16];
+            {
+                const float *vsp = reinterpret_cast<const float *>(bufc + St::kVScale) + pos;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 c = *reinterpret_cast<const float4 *>(vsp + 4 * g);
+                    v_scale[4 * g] = c.x; v_scale[4 * g + 1] = c.y; v_scale[4 * g + 2] = c.z; v_scale[4 * g + 3] = c.w;
+                }
+            }
+            uint32_t zh[8], zl[8];
+            {
+                const u32x4 h0 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzHi + pos / 2);
+                const u32x4 h1 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzHi + pos / 2 + 4);
+                const u32x4 l0 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzLo + pos / 2);
+                const u32x4 l1 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzLo + pos / 2 + 4);
+                zh[0] = h0.x; zh[1] = h0.y; zh[2] = h0.z; zh[3] = h0.w; zh[4] = h1.x; zh[5] = h1.y; zh[6] = h1.z; zh[7] = h1.w;
+                zl[0] = l0.x; zl[1] = l0.y; zl[2] = l0.z; zl[3] = l0.w; zl[4] = l1.x; zl[5] = l1.y; zl[6] = l1.z; zl[7] = l1.w;
+            }
+            uint32_t off = lo_off;
+            asm volatile("" : "+v"(off));
+            const uint32_t *qlo = q_stage + off;
+            f32x16 zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+            sn[0] = mfma_bf16(cop, rowop[0], zero);
+            sn[1] = mfma_bf16(cop, rowop[1], zero);
+            float lsum[2] = {0.0f, 0.0f}, tacc[2] = {0.0f, 0.0f};
+            uint32_t pw[2][8];
+            static_for<8>([&](auto s_) {
+                constexpr int SLAB = decltype(s_)::value;
+                const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
+                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(qlo + 8 * SLAB);
+                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * SLAB);
+                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
+                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
+                sn[0] = mfma_f16(kop, lo0, sn[0]);
+                sn[1] = mfma_f16(kop, lo1, sn[1]);
+                constexpr int RB = SLAB / 4, I0 = 2 * (SLAB % 4);
+#pragma unroll
+                for (int i = I0; i < I0 + 2; ++i) {
+                    const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
+                    const float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
+                    lsum[RB] += p0 + p1;
+                    pw[RB][i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
+                    tacc[RB] = dot2_bf16(pw[RB][i], zh[i], tacc[RB]);
+                    tacc[RB] = dot2_bf16(pw[RB][i], zl[i], tacc[RB]);
+                }
+                KVQ_CHUNK_FENCE();
+            });
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                l_s[rb] += lsum[rb];
+                tau[rb] += tacc[rb];
+                pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
+                pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
+            }
+            uint32_t vw[WPL];
+            {
+                const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
+#pragma unroll
+                for (int i = 0; i < WPL / 4; ++i) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                    vw[4 * i] = w.x; vw[4 * i + 1] = w.y; vw[4 * i + 2] = w.z; vw[4 * i + 3] = w.w;
+                }
+            }
+            float k_scale[16];
+            {
+                const float *ks = reinterpret_cast<const float *>(bufn + St::kKScale) + tln * 32 + hh * 16;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 c = *reinterpret_cast<const float4 *>(ks + 4 * g);
+                    k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
+                }
+            }
+            float mx[2] = {-INFINITY, -INFINITY};
+            static_for<4>([&](auto b_) {
+                constexpr int B = decltype(b_)::value;
+                const u32x4 v0 = value_operand<BITS, B, 0>(vw, uc);
+                const u32x4 v1 = value_operand<BITS, B, 1>(vw, uc);
+                o[B][0] = mfma_bf16(v0, pop[0][0], o[B][0]);
+                o[B][1] = mfma_bf16(v0, pop[1][0], o[B][1]);
+                o[B][0] = mfma_bf16(v1, pop[0][1], o[B][0]);
+                o[B][1] = mfma_bf16(v1, pop[1][1], o[B][1]);
+                constexpr int RB = B / 2, V0 = 8 * (B % 2);
+#pragma unroll
+                for (int v = V0; v < V0 + 8; ++v) e[RB][v] = fmaf(k_scale[v], sn[RB][v], -m_ref[RB]);
+#pragma unroll
+                for (int v = V0; v < V0 + 8; v += 2) mx[RB] = fmaxf(mx[RB], fmaxf(e[RB][v], e[RB][v + 1]));
+                KVQ_CHUNK_FENCE();
+            });
+            tmax[0] = max_halves(mx[0]);
+            tmax[1] = max_halves(mx[1]);
+        };
         // A stage becomes visible one tile before its first tile is scored.
         auto open_stage = [&](int stage) {
             commit(stage);
@@ -603,10 +725,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     break;
                 }
                 if (((t + 1) & 3) == 0) open_stage((t + 1) >> 2);
-                score_tile(t + 1, sn);
-                exp_tile(t, e, pop);
-                pv_tile(t, pop);
-                finalize_tile(t + 1, sn, e, tmax);
+                fused_iteration(t, sn, e, tmax, pop);
                 ++t;
                 if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
             }

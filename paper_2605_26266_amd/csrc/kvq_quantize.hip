@@ -211,6 +211,193 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
     }
 }
 
+// head_dim 128 variant, the shape of every benchmark config.  Same arithmetic, cheaper data movement:
+// after the four butterfly stages inside the lane the 8 lanes of a vector exchange their 16 doubles
+// through a padded LDS row (8 conflict-free 16-byte writes and reads per lane), after which lane l
+// holds channels 16 j + 2 l + e (j = 0..7, e = 0, 1) and the last three stages run inside the lane as
+// well.  In that order a lane owns exactly one register position (reg = l mod 4, half = l / 4) of every
+// 16-wide slab of the key tile, so the key words are built with compile-time shifts and merged across the
+// 4 lanes of a quad with DPP.
+__device__ inline uint32_t quad_or(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
+    return v;
+}
+
+template <int BITS, typename T>
+__global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, const T *__restrict__ k,
+                                                                const T *__restrict__ v, int64_t old_len,
+                                                                int64_t n_tokens, int64_t stride_token,
+                                                                int64_t stride_head)
+{
+    constexpr int D = 128;
+    constexpr int WPL = D * BITS / 64;
+    constexpr int L = (1 << BITS) - 1;
+    constexpr int CPW = 32 / BITS;
+    constexpr int kRowDoubles = D + 16;   // each 16-channel chunk is followed by 2 doubles of padding
+    __shared__ __align__(16) double xpose[kTileTokens][kRowDoubles];
+    __shared__ __align__(16) uint8_t v_stage[kTileTokens][D];
+
+    const int head = blockIdx.y;
+    const int64_t tile = old_len / kTileTokens + blockIdx.x;
+    const int64_t tile_t0 = tile * kTileTokens;
+    const int64_t lo_t = old_len > tile_t0 ? old_len : tile_t0;
+    const int64_t end_all = old_len + n_tokens;
+    const int64_t hi_t = end_all < tile_t0 + kTileTokens ? end_all : tile_t0 + kTileTokens;
+    const int row = threadIdx.x >> 3, l8 = threadIdx.x & 7;
+    const int reg = l8 & 3, hh = l8 >> 2;
+    const int64_t t = tile_t0 + row;
+    const bool valid = t >= lo_t && t < hi_t;
+    const bool tail = t >= hi_t;
+    const int64_t meta_idx = (int64_t)head * cv.cap_tiles * kTileTokens + t;
+    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    double *rowbuf = xpose[row];
+
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        double x[16];
+        if (valid) {
+            const T *src = (pass == 0 ? k : v) + (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * 16;
+            Vec<T>::template load<16>(src, x);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = 0.0;
+        }
+#pragma unroll
+        for (int h = 1; h < 16; h <<= 1) {   // channel bits 0..3
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if ((i & h) == 0) {
+                    const double a = x[i], b = x[i + h];
+                    x[i] = a + b;
+                    x[i + h] = a - b;
+                }
+        }
+        // Exchange inside the vector's 8 lanes (same wavefront: LDS operations of a wave complete in order).
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            double2 w;
+            w.x = x[2 * i];
+            w.y = x[2 * i + 1];
+            *reinterpret_cast<double2 *>(rowbuf + 18 * l8 + 2 * i) = w;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const double2 w = *reinterpret_cast<const double2 *>(rowbuf + 18 * j + 2 * l8);
+            x[2 * j] = w.x;       // channel 16 j + 2 l8
+            x[2 * j + 1] = w.y;   // channel 16 j + 2 l8 + 1
+        }
+#pragma unroll
+        for (int h = 2; h < 16; h <<= 1) {   // channel bits 4..6 = bits 1..3 of the register index
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if ((i & h) == 0) {
+                    const double a = x[i], b = x[i + h];
+                    x[i] = a + b;
+                    x[i + h] = a - b;
+                }
+        }
+        // No NaNs can occur here (finite inputs, exact sums), so min/max are plain selections.
+        double lo = __builtin_fmin(x[0], x[1]), hi = __builtin_fmax(x[0], x[1]);
+#pragma unroll
+        for (int i = 2; i < 16; ++i) {
+            lo = __builtin_fmin(lo, x[i]);
+            hi = __builtin_fmax(hi, x[i]);
+        }
+#pragma unroll
+        for (int msk = 1; msk < 8; msk <<= 1) {
+            lo = __builtin_fmin(lo, __shfl_xor(lo, msk));
+            hi = __builtin_fmax(hi, __shfl_xor(hi, msk));
+        }
+        if (hi == lo) {  // constant vector: widen the range to include 0
+            lo = lo > 0.0 ? 0.0 : lo;
+            hi = hi < 0.0 ? 0.0 : hi;
+        }
+        const bool degenerate = hi == lo;  // all-zero vector
+        const double range = hi - lo;
+        const double inv = degenerate ? 0.0 : (double)L / range;
+        const double step = degenerate ? 0.0 : range / (double)L;
+        const double z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+        // round(u * inv) + z and the clamp are exact in 32-bit integers (|z| + L < 2^31 by the documented
+        // domain), so they give the same codes as the double-precision statement of Eq. 1.
+        const int zi = (int)z;
+        uint32_t code[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int c = (int)__builtin_rint(x[i] * inv) + zi;
+            code[i] = (uint32_t)(c < 0 ? 0 : (c > L ? L : c));   // one v_med3_i32
+        }
+        const float scale = (float)(step * 0.08838834764831845);  // 1/sqrt(128) rounded to double
+        const float zero = (float)z;
+
+        if (pass == 0) {
+            // register index 2 j + e <-> slab j, element pair position `reg`, half `hh`
+            if (BITS == 2) {
+                uint32_t w[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t base = code[4 * q] | (code[4 * q + 1] << 16) | (code[4 * q + 2] << 8) | (code[4 * q + 3] << 24);
+                    w[q] = quad_or(base << (2 * reg));
+                }
+                if ((valid || tail) && reg == 0) {
+                    uint4 out;
+                    out.x = w[0]; out.y = w[1]; out.z = w[2]; out.w = w[3];
+                    *reinterpret_cast<uint4 *>(k_tile + (hh * 32 + row) * WPL) = out;
+                }
+            } else {
+                uint32_t w[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = quad_or((code[2 * j] | (code[2 * j + 1] << 16)) << (4 * reg));
+                if ((valid || tail) && reg < 2) {
+                    uint4 out;
+                    out.x = reg ? w[4] : w[0]; out.y = reg ? w[5] : w[1];
+                    out.z = reg ? w[6] : w[2]; out.w = reg ? w[7] : w[3];
+                    *reinterpret_cast<uint4 *>(k_tile + (hh * 32 + row) * WPL + 4 * reg) = out;
+                }
+            }
+            if (valid || tail) {
+                if (l8 == 2) cv.k_scale[meta_idx] = scale;
+                if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                *reinterpret_cast<uint16_t *>(&v_stage[row][16 * j + 2 * l8]) = (uint16_t)(code[2 * j] | (code[2 * j + 1] << 8));
+            if (valid || tail) {
+                if (l8 == 2) cv.v_scale[meta_idx] = scale;
+                if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+            }
+        }
+    }
+    __syncthreads();
+    // Assemble the value tile: word (lane slot, q) gathers CPW codes of one channel.
+    const int t_keep = (int)(lo_t - tile_t0);
+    const int t_new_end = (int)(hi_t - tile_t0);
+    for (int w = threadIdx.x; w < 64 * WPL; w += 256) {
+        const int lane = w / WPL, q = w % WPL;
+        const int vh = lane >> 5, r = lane & 31;
+        const int blk = BITS == 2 ? q : q >> 1;
+        const int c = 32 * blk + r;
+        uint32_t word = 0u, fresh = 0u, keep = 0u;
+#pragma unroll
+        for (int p = 0; p < CPW; ++p) {
+            const int j = p % (CPW / 2), e = p / (CPW / 2);
+            const int s = BITS == 2 ? (j >> 2) : (q & 1);
+            const int rg = j & 3;
+            const int tok = 16 * s + 8 * (rg >> 1) + 4 * vh + 2 * (rg & 1) + e;
+            const int shift = BITS * j + 16 * e;
+            word |= (uint32_t)v_stage[tok][c] << shift;
+            fresh |= (tok >= t_keep && tok < t_new_end ? (uint32_t)L : 0u) << shift;   // tokens of this append
+            keep |= (tok < t_keep ? (uint32_t)L : 0u) << shift;                        // tokens of earlier appends
+        }
+        word &= fresh;
+        if (keep) word |= v_tile[w] & keep;
+        v_tile[w] = word;
+    }
+}
+
 template <int D, int BITS>
 __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int64_t start, int64_t count,
                                                   uint8_t *codes, float *scales, float *zeros)
@@ -244,8 +431,12 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
     const int64_t first_tile = old_len / kTileTokens;
     const int64_t last_tile = (old_len + n - 1) / kTileTokens;
     const dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)cv.num_heads);
-    hipLaunchKernelGGL((quantize_append_kernel<D, BITS, T>), grid, dim3(256), 0, stream, cv,
-                       static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
+    if constexpr (D == 128)
+        hipLaunchKernelGGL((quantize_append_kernel128<BITS, T>), grid, dim3(256), 0, stream, cv,
+                           static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
+    else
+        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, T>), grid, dim3(256), 0, stream, cv,
+                           static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
     return hipGetLastError();
 }
 

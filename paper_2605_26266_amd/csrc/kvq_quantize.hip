@@ -36,6 +36,47 @@ template <> struct Vec<uint16_t> {  // bf16
         }
     }
 };
+// Raw 16-element loads that are issued for K and V up front and widened to double when needed.
+template <typename T> struct Raw16;
+template <> struct Raw16<uint16_t> {
+    uint4 w[2];
+    __device__ void load(const uint16_t *p) { w[0] = reinterpret_cast<const uint4 *>(p)[0]; w[1] = reinterpret_cast<const uint4 *>(p)[1]; }
+    __device__ void zero() { w[0] = make_uint4(0, 0, 0, 0); w[1] = w[0]; }
+    __device__ void widen(double (&x)[16]) const
+    {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t ws[4] = {w[i].x, w[i].y, w[i].z, w[i].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[8 * i + 2 * j] = (double)__uint_as_float(ws[j] << 16);
+                x[8 * i + 2 * j + 1] = (double)__uint_as_float(ws[j] & 0xffff0000u);
+            }
+        }
+    }
+};
+template <> struct Raw16<float> {
+    float4 w[4];
+    __device__ void load(const float *p)
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = reinterpret_cast<const float4 *>(p)[i];
+    }
+    __device__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    __device__ void widen(double (&x)[16]) const
+    {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[4 * i] = (double)w[i].x; x[4 * i + 1] = (double)w[i].y;
+            x[4 * i + 2] = (double)w[i].z; x[4 * i + 3] = (double)w[i].w;
+        }
+    }
+};
+
 template <> struct Vec<float> {
     template <int N> __device__ static void load(const float *p, double (&x)[N])
     {
@@ -255,16 +296,21 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
     uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
     double *rowbuf = xpose[row];
 
-#pragma unroll 1
+    // Both loads are in flight before any arithmetic starts.
+    Raw16<T> raw_k, raw_v;
+    if (valid) {
+        const int64_t off = (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * 16;
+        raw_k.load(k + off);
+        raw_v.load(v + off);
+    } else {
+        raw_k.zero();
+        raw_v.zero();
+    }
+#pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         double x[16];
-        if (valid) {
-            const T *src = (pass == 0 ? k : v) + (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * 16;
-            Vec<T>::template load<16>(src, x);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) x[i] = 0.0;
-        }
+        if (pass == 0) raw_k.widen(x);
+        else raw_v.widen(x);
 #pragma unroll
         for (int h = 1; h < 16; h <<= 1) {   // channel bits 0..3
 #pragma unroll
@@ -372,28 +418,35 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
         }
     }
     __syncthreads();
-    // Assemble the value tile: word (lane slot, q) gathers CPW codes of one channel.
+    // Assemble the value tile: word (lane slot, q) gathers CPW codes of one channel.  Rows that this
+    // append does not own staged zeros, so only a tile begun by an earlier append needs merging.
     const int t_keep = (int)(lo_t - tile_t0);
-    const int t_new_end = (int)(hi_t - tile_t0);
     for (int w = threadIdx.x; w < 64 * WPL; w += 256) {
         const int lane = w / WPL, q = w % WPL;
         const int vh = lane >> 5, r = lane & 31;
         const int blk = BITS == 2 ? q : q >> 1;
         const int c = 32 * blk + r;
-        uint32_t word = 0u, fresh = 0u, keep = 0u;
+        uint32_t word = 0u;
 #pragma unroll
         for (int p = 0; p < CPW; ++p) {
             const int j = p % (CPW / 2), e = p / (CPW / 2);
             const int s = BITS == 2 ? (j >> 2) : (q & 1);
             const int rg = j & 3;
             const int tok = 16 * s + 8 * (rg >> 1) + 4 * vh + 2 * (rg & 1) + e;
-            const int shift = BITS * j + 16 * e;
-            word |= (uint32_t)v_stage[tok][c] << shift;
-            fresh |= (tok >= t_keep && tok < t_new_end ? (uint32_t)L : 0u) << shift;   // tokens of this append
-            keep |= (tok < t_keep ? (uint32_t)L : 0u) << shift;                        // tokens of earlier appends
+            word |= (uint32_t)v_stage[tok][c] << (BITS * j + 16 * e);
         }
-        word &= fresh;
-        if (keep) word |= v_tile[w] & keep;
+        if (t_keep > 0) {   // uniform over the workgroup
+            uint32_t keep = 0u;
+#pragma unroll
+            for (int p = 0; p < CPW; ++p) {
+                const int j = p % (CPW / 2), e = p / (CPW / 2);
+                const int s = BITS == 2 ? (j >> 2) : (q & 1);
+                const int rg = j & 3;
+                const int tok = 16 * s + 8 * (rg >> 1) + 4 * vh + 2 * (rg & 1) + e;
+                keep |= (tok < t_keep ? (uint32_t)L : 0u) << (BITS * j + 16 * e);
+            }
+            word |= v_tile[w] & keep;
+        }
         v_tile[w] = word;
     }
 }

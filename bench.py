@@ -34,42 +34,106 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large", choices=["small", "mid", "large"])
+    ap.add_argument("--workload", default="large", choices=["small", "mid", "large", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=768, help="query rows of one head given to the CPU oracle")
+    ap.add_argument("--cpu-heads", type=int, default=8, help="heads (all query rows each) given to the CPU oracle")
     return ap.parse_args()
 
 
-def cpu_baseline(w, wl, rows_wanted):
-    """The oracle, as it stands, on one head and a seeded subset of query rows (all keys)."""
+def cpu_baseline(w, wl, n_heads):
+    """The oracle, as it stands, on the first `n_heads` heads of the workload (all query rows, all keys)."""
     import oracle
-    head = [0]
-    rows = wl.sample_rows(w, rows_wanted)
-    ks, vs = zip(*[wl.chunk_kv(w, c, head) for c in range(w.cached_chunks)])
-    kc, vc = np.concatenate(ks)[:, 0].astype(np.float64), np.concatenate(vs)[:, 0].astype(np.float64)
-    kr, vr = wl.chunk_kv(w, w.cached_chunks, head)
-    q = wl.chunk_q(w, head)[rows][:, 0]
-    t0 = time.perf_counter()
-    k_codes, k_scale, k_zero = oracle.quantize(kc, w.bits)
-    v_codes, v_scale, v_zero = oracle.quantize(vc, w.bits)
-    t_quant = time.perf_counter() - t0
-    khat, vhat = oracle.dequantize(k_codes, k_scale, k_zero), oracle.dequantize(v_codes, v_scale, v_zero)
-    t0 = time.perf_counter()
-    oracle.attention(q, khat, k_scale, vhat, kr[:, 0], vr[:, 0], correction=1)
-    t_att = time.perf_counter() - t0
-    n_keys = kc.shape[0] + kr.shape[0]
-    flop = 4.0 * len(rows) * n_keys * w.head_dim
-    quant_rows = 2 * kc.shape[0]
+    n_heads = min(n_heads, w.num_heads)
+    t_att = t_quant = 0.0
+    quant_rows = 0
+    for h in range(n_heads):
+        ks, vs = zip(*[wl.chunk_kv(w, c, [h]) for c in range(w.cached_chunks)])
+        kc, vc = np.concatenate(ks)[:, 0].astype(np.float64), np.concatenate(vs)[:, 0].astype(np.float64)
+        kr, vr = wl.chunk_kv(w, w.cached_chunks, [h])
+        q = wl.chunk_q(w, [h])[:, 0]
+        t0 = time.perf_counter()
+        k_codes, k_scale, k_zero = oracle.quantize(kc, w.bits)
+        v_codes, v_scale, v_zero = oracle.quantize(vc, w.bits)
+        t_quant += time.perf_counter() - t0
+        quant_rows += 2 * kc.shape[0]
+        khat, vhat = oracle.dequantize(k_codes, k_scale, k_zero), oracle.dequantize(v_codes, v_scale, v_zero)
+        t0 = time.perf_counter()
+        oracle.attention(q, khat, k_scale, vhat, kr[:, 0], vr[:, 0], correction=1)
+        t_att += time.perf_counter() - t0
+    n_keys = w.cached_tokens + w.chunk_tokens
+    flop = 4.0 * n_heads * w.chunk_tokens * n_keys * w.head_dim
     return {
         "value": flop / t_att / 1e12,
         "unit": "TFLOP/s",
         "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": "attention: 1 head x %d seeded query rows x all %d keys of the %s config (%.1f s); "
-                  "quantizer: %d vectors of that head (%.1f s)" % (len(rows), n_keys, w.name, t_att, quant_rows, t_quant),
+        "sample": "attention: %d of %d heads x all %d query rows x all %d keys of the %s config (%.1f s); "
+                  "quantizer: the %d cached K/V vectors of those heads (%.1f s)"
+                  % (n_heads, w.num_heads, w.chunk_tokens, n_keys, w.name, t_att, quant_rows, t_quant),
         "attention_seconds": t_att,
         "quantize_rows_per_s": quant_rows / t_quant,
         "quantize_gb_per_s_equiv": quant_rows * (w.quantize_bytes(1) / (2 * w.num_heads)) / t_quant / 1e9,
+    }
+
+
+def run_stream(args, torch, B, wl):
+    """Stream config: one 4096-token chunk appended 32 times, corrected attention after every append."""
+    w = wl.WORKLOADS["stream"]
+    dev = "cuda:0"
+
+    def up(x):
+        return torch.from_numpy(x).to(dev).to(torch.bfloat16)
+
+    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16), dev)
+    k, v = (up(x) for x in wl.chunk_kv(w, 0))
+    q = up(wl.chunk_q(w))
+    out = torch.empty_like(q)
+    T = w.cached_chunks
+
+    def one_pass(events=None):
+        B.kvq_cache_reset(cache)
+        for t in range(T):
+            if events:
+                events[t][0].record()
+            B.kvq_quantize_append(cache, k, v)
+            if events:
+                events[t][1].record()
+            B.kvq_chunk_attention(cache, 0, (t + 1) * w.chunk_tokens, q, k, v, out, None, 0.0, 1)
+            if events:
+                events[t][2].record()
+
+    for _ in range(max(1, args.warmup // 2)):
+        one_pass()
+    torch.cuda.synchronize()
+    steps = max(1, args.steps // 4)
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(T)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        one_pass(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_q = np.array([[e[0].elapsed_time(e[1]) for e in p] for p in ev]).mean(axis=0)
+    t_a = np.array([[e[1].elapsed_time(e[2]) for e in p] for p in ev]).mean(axis=0)
+    flop_t = np.array([4.0 * w.num_heads * w.chunk_tokens * ((t + 2) * w.chunk_tokens) * w.head_dim for t in range(T)])
+    total_flop = float(flop_t.sum())
+    ms_per_step = wall * 1e3 / steps
+    att_tf = total_flop / (t_a.sum() * 1e-3) / 1e12
+    return {
+        "metric": "corrected INT2-KV chunk-attention TFLOP/s (+ % MFMA peak); quantize GB/s",
+        "value": total_flop / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": max(1, args.warmup // 2), "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "stream: 48 heads, head_dim 128, one 4096-token chunk appended 32 times to the INT2 cache "
+                               "(131072 tokens), corrected attention from the chunk's queries after every append",
+                   "step": "32 x (quantize_append + chunk_attention)"},
+        "quantize_us_per_append": float(t_q.mean() * 1e3),
+        "quantize_gb_per_s": w.quantize_bytes() / (t_q.mean() * 1e-3) / 1e9,
+        "per_chunk_latency_ms": [float(a + b) for a, b in zip(t_q, t_a)],
+        "attention_tflops": att_tf,
+        "pct_mfma_peak": 100.0 * att_tf / MFMA_PEAK_TFLOPS,
+        "roofline": {"kernel": "attention_mfma_kernel<2, true>", "bound": "mfma", "achieved": att_tf,
+                     "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": att_tf / MFMA_PEAK_TFLOPS, "traffic": None},
     }
 
 
@@ -89,6 +153,9 @@ def main():
     B.lib()  # fail loudly when the library is not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.workload == "stream":
+        print(json.dumps(run_stream(args, torch, B, wl)))
+        return
     w = wl.WORKLOADS[args.workload]
     n_cached = w.cached_chunks
 
@@ -186,7 +253,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_rows)
+        result["cpu_baseline"] = cpu_baseline(w, wl, args.cpu_heads)
     print(json.dumps(result))
 
 

@@ -157,6 +157,36 @@ def test_large_sampled_rows(P, correction):
     print("large corr=%d: max err %.2e" % (correction, err))
 
 
+def test_stream_append_then_attend(P):
+    """Stream config: the same 4096-token chunk is appended t times, each append followed by corrected
+    attention from that chunk's queries over the whole cache plus the chunk itself.  Parity on sampled
+    heads x rows after 1, 2 and 32 appends (131072 cached tokens at the end)."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["stream"]
+    heads = [3, 40]
+    cache = P.make_cache(w, w.cached_tokens)
+    k, v = wl.chunk_kv(w, 0)
+    q = wl.chunk_q(w)
+    kd, vd, qd = P.to_dev(k, "bf16"), P.to_dev(v, "bf16"), P.to_dev(q, "bf16")
+    out = torch.empty_like(qd)
+    mass = torch.empty((w.num_heads, w.chunk_tokens), dtype=torch.float32, device=P.DEV)
+    rows = wl.sample_rows(w, 24)
+    ks, vs = k[:, heads], v[:, heads]
+    for t in range(1, w.cached_chunks + 1):
+        B.kvq_quantize_append(cache, kd, vd)
+        B.kvq_chunk_attention(cache, 0, len(cache), qd, kd, vd, out, mass, 0.0, 1)
+        if t in (1, 2, w.cached_chunks):
+            torch.cuda.synchronize()
+            got = out.float().cpu().numpy().astype(np.float64)[rows][:, heads]
+            got_mass = mass.cpu().numpy().astype(np.float64)[heads][:, rows]
+            ref, mass_ref, _ = oracle.chunk_attention(q[rows][:, heads], np.concatenate([ks] * t),
+                                                      np.concatenate([vs] * t), ks, vs, 2, 1)
+            err = P.assert_attention_close(got, got_mass, ref, mass_ref, P.TOL_OUT_BF16, "stream t=%d" % t)
+            print("stream t=%d: max err %.2e, mean P_S %.4f" % (t, err, got_mass.mean()))
+    assert len(cache) == w.cached_tokens
+
+
 def test_argument_errors(P):
     from paper_2605_26266_amd import binding as B, workloads as wl
     w = wl.WORKLOADS["small"]

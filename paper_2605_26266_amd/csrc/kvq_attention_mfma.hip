@@ -11,7 +11,7 @@
 // exactly that lane's B operand of the P*V MFMA -- no shuffle, no LDS round trip for P.
 //
 // Cached keys/values (Alg. 1 of the paper, cached block).  Packed tiles (see kvq_internal.h) are
-// staged through LDS 128 keys at a time (three buffers, one barrier per stage).  A lane pulls its 16
+// staged through LDS 128 keys at a time (four buffers, one barrier per stage).  A lane pulls its 16
 // or 32 bytes of codes and turns every word into MFMA operand registers with one shift and one
 // and-or per register: the code lands in the top mantissa bits of a 16-bit float whose exponent makes
 // the value OFFSET + code (4 + code for 2 bits, 16 + code for 4 bits).  Key codes and the rotated
@@ -69,7 +69,7 @@ constexpr int kRowsPerWave = 64;
 constexpr int kRowsPerBlock = kWaves * kRowsPerWave;  // 256
 constexpr int kStageTiles = 4;
 constexpr int kStageKeys = kStageTiles * kTileTokens;  // 128
-constexpr int kBuffers = 3;
+constexpr int kBuffers = 4;    // power of two: buffer index = stage & 3
 constexpr int kQRowWords = 68;    // 64 words of f16 pairs + 4 words padding (bank spread)
 constexpr int kVtRowWords = 18;   // 32 tokens of bf16 = 16 words + 2 words padding
 constexpr float kLog2e = 1.4426950408889634f;
@@ -589,22 +589,30 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         // One steady-state iteration, interleaved by hand: the score MFMAs of tile t+1 (4 per key slab)
         // next to one eighth of the exponential work of tile t, then the P*V MFMAs of tile t (4 per channel
         // block) next to one quarter of the score scaling of tile t+1.  Nothing crosses a chunk boundary,
-        // so every group of four 32-cycle MFMAs has about as much independent vector work beside it.
-        auto fused_iteration = [&](int t, f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2], u32x4 (&pop)[2][2]) {
+        // so every group of four MFMAs has about as much independent vector work beside it, and every LDS
+        // operand is requested one chunk (or one iteration) before the instruction that consumes it.
+        struct Prefetched {
+            uint32_t kw[WPL];   // packed key codes of the tile scored next
+            u32x4 cop;          // its constant-term operand
+        };
+        auto prefetch_keys = [&](int t, Prefetched &pf) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const int tl = t & 3;
+            const uint32_t *src = buf + St::kK + tl * 64 * WPL + lane * WPL;
+#pragma unroll
+            for (int i = 0; i < WPL / 4; ++i) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                pf.kw[4 * i] = w.x; pf.kw[4 * i + 1] = w.y; pf.kw[4 * i + 2] = w.z; pf.kw[4 * i + 3] = w.w;
+            }
+            pf.cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
+        };
+        auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2],
+                                   u32x4 (&pop)[2][2]) {
             const uint32_t *bufn = lds + (((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
             const uint32_t *bufc = lds + ((t >> 2) % kBuffers) * St::kWords;         // holds tile t
             const int tln = (t + 1) & 3, tlc = t & 3;
-            uint32_t kw[WPL];
-            {
-                const uint32_t *src = bufn + St::kK + tln * 64 * WPL + lane * WPL;
-#pragma unroll
-                for (int i = 0; i < WPL / 4; ++i) {
-                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
-                    kw[4 * i] = w.x; kw[4 * i + 1] = w.y; kw[4 * i + 2] = w.z; kw[4 * i + 3] = w.w;
-                }
-            }
-            const u32x4 cop = *reinterpret_cast<const u32x4 *>(bufn + St::kCop + (tln * 64 + lane) * 4);
             const int pos = tlc * 32 + hh * 16;
+            // requests for this iteration's exponential work
             float v_scale[16];
             {
                 const float *vsp = reinterpret_cast<const float *>(bufc + St::kVScale) + pos;
@@ -626,23 +634,21 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             uint32_t off = lo_off;
             asm volatile("" : "+v"(off));
             const uint32_t *qlo = q_stage + off;
+            u32x4 lo_cur[2], lo_nxt[2];
+            lo_cur[0] = *reinterpret_cast<const u32x4 *>(qlo);
+            lo_cur[1] = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords);
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            sn[0] = mfma_bf16(cop, rowop[0], zero);
-            sn[1] = mfma_bf16(cop, rowop[1], zero);
+            sn[0] = mfma_bf16(pf.cop, rowop[0], zero);
+            sn[1] = mfma_bf16(pf.cop, rowop[1], zero);
             float lsum[2] = {0.0f, 0.0f}, tacc[2] = {0.0f, 0.0f};
             uint32_t pw[2][8];
-            static_for<8>([&](auto s_) {
-                constexpr int SLAB = decltype(s_)::value;
-                const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
-                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(qlo + 8 * SLAB);
-                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * SLAB);
-                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
-                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
-                sn[0] = mfma_f16(kop, lo0, sn[0]);
-                sn[1] = mfma_f16(kop, lo1, sn[1]);
-                constexpr int RB = SLAB / 4, I0 = 2 * (SLAB % 4);
+            uint32_t vw[WPL];
+            float k_scale[16];
+            auto exp_chunk = [&](auto c_) {
+                constexpr int C = decltype(c_)::value;
+                constexpr int RB = C / 4, I0 = 2 * (C % 4);
 #pragma unroll
                 for (int i = I0; i < I0 + 2; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
@@ -652,8 +658,39 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     tacc[RB] = dot2_bf16(pw[RB][i], zh[i], tacc[RB]);
                     tacc[RB] = dot2_bf16(pw[RB][i], zl[i], tacc[RB]);
                 }
+            };
+            KVQ_CHUNK_FENCE();
+            static_for<8>([&](auto s_) {
+                constexpr int SLAB = decltype(s_)::value;
+                if constexpr (SLAB < 7) {   // next slab's low query parts
+                    lo_nxt[0] = *reinterpret_cast<const u32x4 *>(qlo + 8 * (SLAB + 1));
+                    lo_nxt[1] = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * (SLAB + 1));
+                }
+                if constexpr (SLAB == 5) {  // value codes and key scales for the second half of the iteration
+                    const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
+#pragma unroll
+                    for (int i = 0; i < WPL / 4; ++i) {
+                        const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                        vw[4 * i] = w.x; vw[4 * i + 1] = w.y; vw[4 * i + 2] = w.z; vw[4 * i + 3] = w.w;
+                    }
+                    const float *ks = reinterpret_cast<const float *>(bufn + St::kKScale) + tln * 32 + hh * 16;
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float4 c = *reinterpret_cast<const float4 *>(ks + 4 * g);
+                        k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
+                    }
+                }
+                const u32x4 kop = key_operand<BITS, SLAB>(pf.kw, uc);
+                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
+                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
+                sn[0] = mfma_f16(kop, lo_cur[0], sn[0]);
+                sn[1] = mfma_f16(kop, lo_cur[1], sn[1]);
+                if constexpr (SLAB >= 1) exp_chunk(IntC<SLAB - 1>{});
+                lo_cur[0] = lo_nxt[0];
+                lo_cur[1] = lo_nxt[1];
                 KVQ_CHUNK_FENCE();
             });
+            exp_chunk(IntC<7>{});
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 l_s[rb] += lsum[rb];
@@ -661,24 +698,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
                 pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
             }
-            uint32_t vw[WPL];
-            {
-                const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
-#pragma unroll
-                for (int i = 0; i < WPL / 4; ++i) {
-                    const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
-                    vw[4 * i] = w.x; vw[4 * i + 1] = w.y; vw[4 * i + 2] = w.z; vw[4 * i + 3] = w.w;
-                }
-            }
-            float k_scale[16];
-            {
-                const float *ks = reinterpret_cast<const float *>(bufn + St::kKScale) + tln * 32 + hh * 16;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 c = *reinterpret_cast<const float4 *>(ks + 4 * g);
-                    k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
-                }
-            }
+            // key codes of the tile after next (its stage has been opened at the top of this iteration)
+            prefetch_keys(t + 2, pf);
             float mx[2] = {-INFINITY, -INFINITY};
             static_for<4>([&](auto b_) {
                 constexpr int B = decltype(b_)::value;
@@ -692,7 +713,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
 #pragma unroll
                 for (int v = V0; v < V0 + 8; ++v) e[RB][v] = fmaf(k_scale[v], sn[RB][v], -m_ref[RB]);
 #pragma unroll
-                for (int v = V0; v < V0 + 8; v += 2) mx[RB] = fmaxf(mx[RB], fmaxf(e[RB][v], e[RB][v + 1]));
+                for (int v = V0; v < V0 + 8; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
                 KVQ_CHUNK_FENCE();
             });
             tmax[0] = max_halves(mx[0]);
@@ -712,6 +733,9 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         u32x4 pop[2][2];
         score_tile(0, sn);
         finalize_tile(0, sn, e, tmax);
+        if (n_tiles > 4) open_stage(1);   // stages are opened two tiles before their first tile is scored
+        Prefetched pf;
+        prefetch_keys(1, pf);
         int t = 0;
         bool done = false;
         while (!done) {
@@ -724,8 +748,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     done = true;
                     break;
                 }
-                if (((t + 1) & 3) == 0) open_stage((t + 1) >> 2);
-                fused_iteration(t, sn, e, tmax, pop);
+                if (((t + 2) & 3) == 0 && t + 2 >= 8) open_stage((t + 2) >> 2);
+                fused_iteration(t, pf, sn, e, tmax, pop);
                 ++t;
                 if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
             }
@@ -923,11 +947,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     w.y = pack_bf16(o[b][rb][4 * g + 2] * inv, o[b][rb][4 * g + 3] * inv);
                     *reinterpret_cast<u32x2 *>(dst + 32 * b + 8 * g) = w;
                 }
-#ifdef KVQ_DEBUG_DUMP
-            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = KVQ_DEBUG_DUMP == 1 ? m_ref[rb] : KVQ_DEBUG_DUMP == 2 ? ls : KVQ_DEBUG_DUMP == 3 ? tau[rb] : lr;
-#else
             if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = ls * inv;
-#endif
         }
     }
 }

@@ -64,9 +64,14 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 #endif
 
 constexpr int D = 128;
-constexpr int kWaves = 4;
-constexpr int kRowsPerWave = 64;
-constexpr int kRowsPerBlock = kWaves * kRowsPerWave;  // 256
+#ifndef KVQ_ROW_BLOCKS_PER_WAVE
+#define KVQ_ROW_BLOCKS_PER_WAVE 2
+#endif
+constexpr int kRB = KVQ_ROW_BLOCKS_PER_WAVE;          // 32-row blocks owned by one wavefront
+constexpr int kRowsPerWave = 32 * kRB;
+constexpr int kRowsPerBlock = 256;
+constexpr int kWaves = kRowsPerBlock / kRowsPerWave;  // 8 (two per SIMD) or 4
+constexpr int kThreads = 64 * kWaves;
 constexpr int kStageTiles = 4;
 constexpr int kStageKeys = kStageTiles * kTileTokens;  // 128
 constexpr int kBuffers = 4;    // power of two: buffer index = stage & 3
@@ -87,7 +92,8 @@ template <int BITS> struct Stage {
     static constexpr int kVScale = kKScale + kStageKeys;        // [tile][hh][16]   float
     static constexpr int kVzHi = kVScale + kStageKeys;          // [tile][hh][8]    bf16 pairs
     static constexpr int kVzLo = kVzHi + kStageKeys / 2;
-    static constexpr int kWords = kVzLo + kStageKeys / 2;
+    static constexpr int kFlags = kVzLo + kStageKeys / 2;       // 2 words: "some low zero-point part is nonzero"
+    static constexpr int kWords = kFlags + 4;
 };
 
 template <int BITS> constexpr size_t lds_bytes()
@@ -215,7 +221,7 @@ template <int N, typename F> __device__ inline void static_for(F &&f)
 }
 
 template <int BITS, bool CORR>
-__global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
+__global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
 {
     using St = Stage<BITS>;
     constexpr int WPL = St::WPL;
@@ -248,17 +254,19 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     const UnpackConsts uc = make_unpack_consts<BITS>();
 
     // ---------------------------------------------------------------- query preparation ----
-    // Lane r of the wave rotates query row wave_row0 + r: q~ = Hn q * softmax_scale * log2(e), split
-    // into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
-    uint32_t *my_q = q_stage + (wave * kRowsPerWave) * kQRowWords;
-    u32x4 qop[2][8];  // B operands of the score MFMA: lane (n, hh) holds channels 16*slab + 8*hh .. +7 of rows n, n + 32
+    // kPrepLanes adjacent lanes rotate one query row of the block: q~ = Hn q * softmax_scale * log2(e),
+    // split into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
+    constexpr int kPrepLanes = kThreads / kRowsPerBlock;   // 1 or 2
+    constexpr int kPrepCh = D / kPrepLanes;                 // channels per lane
+    u32x4 qop[kRB][8];  // B operands of the score MFMA: lane (n, hh) holds channels 16*slab + 8*hh .. +7 of rows n + 32 rb
     {
-        int64_t row = wave_row0 + lane;
+        const int prow = tid / kPrepLanes, ppart = tid % kPrepLanes;
+        int64_t row = (int64_t)rblk * kRowsPerBlock + prow;
         row = row < a.m ? row : a.m - 1;
-        const uint4 *src = reinterpret_cast<const uint4 *>(q_base + row * a.stride_token);
-        float x[D];
+        const uint4 *src = reinterpret_cast<const uint4 *>(q_base + row * a.stride_token + ppart * kPrepCh);
+        float x[kPrepCh];
 #pragma unroll
-        for (int i = 0; i < D / 8; ++i) {
+        for (int i = 0; i < kPrepCh / 8; ++i) {
             const uint4 w = src[i];
             const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -269,11 +277,11 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         }
         float nu = 0.0f;
 #pragma unroll
-        for (int i = 0; i < D; ++i) nu = fmaf(x[i], x[i], nu);
+        for (int i = 0; i < kPrepCh; ++i) nu = fmaf(x[i], x[i], nu);
 #pragma unroll
-        for (int h = 1; h < D; h <<= 1) {
+        for (int h = 1; h < kPrepCh; h <<= 1) {
 #pragma unroll
-            for (int i = 0; i < D; ++i) {
+            for (int i = 0; i < kPrepCh; ++i) {
                 if ((i & h) == 0) {
                     const float p = x[i], q2 = x[i + h];
                     x[i] = p + q2;
@@ -281,42 +289,55 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 }
             }
         }
-        const float cq = c_log * 0.088388347648318f;
-        float ssum = 0.0f;
-        uint32_t whi[D / 2], wlo[D / 2];
+        if constexpr (kPrepLanes == 2) {   // last butterfly stage: between the two lanes of the row
+            nu += __shfl_xor(nu, 1);
 #pragma unroll
-        for (int i = 0; i < D / 2; ++i) {
-            const float v0 = x[2 * i] * cq, v1 = x[2 * i + 1] * cq;
-            whi[i] = pack_f16(v0, v1);
-            const float h0 = f16_lo(whi[i]), h1 = f16_hi(whi[i]);
-            wlo[i] = pack_f16(v0 - h0, v1 - h1);
-            ssum += (h0 + f16_lo(wlo[i])) + (h1 + f16_hi(wlo[i]));
+            for (int i = 0; i < kPrepCh; ++i) {
+                const float other = __shfl_xor(x[i], 1);
+                x[i] = ppart ? other - x[i] : x[i] + other;
+            }
         }
-        row_scal[2 * (wave * kRowsPerWave + lane)] = ssum;
-        row_scal[2 * (wave * kRowsPerWave + lane) + 1] =
-            CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
+        const float cq = c_log * 0.088388347648318f;
+#pragma unroll
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq;
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
-        uint32_t *dst = my_q + lane * kQRowWords;
+        uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
 #pragma unroll
-        for (int i = 0; i < D / 8; ++i) {
+        for (int i = 0; i < kPrepCh / 8; ++i) {
             u32x4 w;
-            w.x = whi[4 * i]; w.y = whi[4 * i + 1]; w.z = whi[4 * i + 2]; w.w = whi[4 * i + 3];
+            w.x = pack_f16(x[8 * i], x[8 * i + 1]); w.y = pack_f16(x[8 * i + 2], x[8 * i + 3]);
+            w.z = pack_f16(x[8 * i + 4], x[8 * i + 5]); w.w = pack_f16(x[8 * i + 6], x[8 * i + 7]);
             *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
         }
         __syncthreads();
-        const uint32_t *hsrc = my_q + n * kQRowWords + 4 * hh;
+        const uint32_t *hsrc = q_stage + (wave * kRowsPerWave + n) * kQRowWords + 4 * hh;
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int s = 0; s < 8; ++s)
                 qop[rb][s] = *reinterpret_cast<const u32x4 *>(hsrc + 32 * rb * kQRowWords + 8 * s);
         __syncthreads();
+        float ssum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < D / 8; ++i) {
+        for (int i = 0; i < kPrepCh / 8; ++i) {
+            uint32_t lo[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float v0 = x[8 * i + 2 * j], v1 = x[8 * i + 2 * j + 1];
+                const uint32_t hi = pack_f16(v0, v1);
+                const float h0 = f16_lo(hi), h1 = f16_hi(hi);
+                lo[j] = pack_f16(v0 - h0, v1 - h1);
+                ssum += (h0 + f16_lo(lo[j])) + (h1 + f16_hi(lo[j]));
+            }
             u32x4 w;
-            w.x = wlo[4 * i]; w.y = wlo[4 * i + 1]; w.z = wlo[4 * i + 2]; w.w = wlo[4 * i + 3];
+            w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
             *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+        }
+        if constexpr (kPrepLanes == 2) ssum += __shfl_xor(ssum, 1);
+        if (ppart == 0) {
+            row_scal[2 * prow] = ssum;
+            row_scal[2 * prow + 1] = CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
         }
     }
     __syncthreads();
@@ -324,9 +345,9 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     // -(OFFSET + zero) pieces and the mask bias, lane half 1 the key's scale pieces:
     //   hh = 0: [S_h, S_m, S_l, S_h, S_m, S_l, 1, 0]   S  = sum_c q~_c  in three bf16 pieces
     //   hh = 1: [N_h, N_l, N_h, N_l, 0, 0, 0, 0]       N  = -nu'        in two bf16 pieces
-    u32x4 rowop[2];
+    u32x4 rowop[kRB];
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < kRB; ++rb) {
         const float ssum = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n)];
         const float nnu = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n) + 1];
         const uint16_t s_h = bf16_bits(ssum);
@@ -346,15 +367,15 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     // The 64 registers of query operands live in accumulation registers (MFMA reads them from there
     // directly), which leaves the vector registers to the score tile in flight.
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
+    for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
 
-    f32x16 o[4][2];
+    f32x16 o[4][kRB];
 #pragma unroll
     for (int b = 0; b < 4; ++b)
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[b][rb][v] = 0.0f;
     // Keeps the 128 output accumulators in accumulation registers at the points where the fast loops
@@ -363,17 +384,17 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) asm volatile("" : "+a"(o[b][rb]));
+            for (int rb = 0; rb < kRB; ++rb) asm volatile("" : "+a"(o[b][rb]));
     };
-    float m_ref[2] = {0.0f, 0.0f};      // reference maximum (log2 domain); set by the first tile
-    float l_s[2] = {0.0f, 0.0f}, l_r[2] = {0.0f, 0.0f}, tau[2] = {0.0f, 0.0f};
+    float m_ref[kRB] = {};              // reference maximum (log2 domain); set by the first tile
+    float l_s[kRB] = {}, l_r[kRB] = {}, tau[kRB] = {};
     bool first = true;                  // no tile has set the reference yet
 
     // Leaves the fast loops: move the reference of the rows whose pending tile maximum `tmax` (relative
     // to the old reference) is too large, and rescale what has been accumulated so far.
-    auto move_reference = [&](float (&e)[2][16], const float (&tmax)[2]) {
+    auto move_reference = [&](float (&e)[kRB][16], const float (&tmax)[kRB]) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
             const bool mv = first || tmax[rb] > kRescaleThreshold;
             const float delta = mv ? tmax[rb] : 0.0f;
             const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta);
@@ -392,6 +413,13 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         pin_accumulators();
     };
 
+    auto over_threshold = [&](const float (&tmax)[kRB]) {
+        bool over = false;
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) over = over || tmax[rb] > kRescaleThreshold;
+        return over;
+    };
+
     // ---------------------------------------------------------------------- cached keys ----
     if (a.cache_len > 0) {
         const int64_t cs = a.cache_start, ce = a.cache_start + a.cache_len;
@@ -403,23 +431,25 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         const int64_t cap_tokens = cv.cap_tiles * kTileTokens;
 
         // ---- loader: global -> registers (prefetch), registers -> LDS (commit, builds the constants)
-        constexpr int kCodeIters = St::kCodeWords / 4 / 256;   // 16-byte vectors per thread and tensor
-        u32x4 pre_k[kCodeIters], pre_v[kCodeIters];
+        constexpr int kCodeVecs = St::kCodeWords / 4;               // 16-byte vectors per tensor and stage
+        constexpr int kCodeIters = 2 * kCodeVecs / kThreads;        // vectors per thread (keys, then values)
+        u32x4 pre_kv[kCodeIters];
         float pre_a = 0.0f, pre_b = 0.0f, pre_c = 0.0f;
         bool pre_valid = false;
-        const int ld_key = tid & 127, ld_half = tid >> 7;       // one (key, operand half) per thread
+        const int ld_key = tid & 127, ld_half = (tid >> 7) & 1; // one (key, operand half) per thread below 256
+        const bool ld_meta = tid < 2 * kStageKeys;
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
             const int64_t tile0 = t_first + (int64_t)stage * kStageTiles;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
-                const int vec = tid + 256 * it;
+                const int g = tid + kThreads * it, vec = g % kCodeVecs;
                 int64_t tile = tile0 + vec / (16 * WPL);
                 tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // never read past the storage
                 const int64_t word = (head_tile0 + tile) * (64 * WPL) + (vec % (16 * WPL)) * 4;
-                pre_k[it] = *reinterpret_cast<const u32x4 *>(cv.k_codes + word);
-                pre_v[it] = *reinterpret_cast<const u32x4 *>(cv.v_codes + word);
+                pre_kv[it] = *reinterpret_cast<const u32x4 *>((g < kCodeVecs ? cv.k_codes : cv.v_codes) + word);
             }
+            if (!ld_meta) return;
             int64_t tok = tile0 * kTileTokens + ld_key;
             pre_valid = tok >= cs && tok < ce;
             tok = tok < cap_tokens ? tok : cap_tokens - 1;
@@ -437,10 +467,10 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             uint32_t *buf = lds + (stage % kBuffers) * St::kWords;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
-                const int vec = tid + 256 * it;
-                *reinterpret_cast<u32x4 *>(buf + St::kK + 4 * vec) = pre_k[it];
-                *reinterpret_cast<u32x4 *>(buf + St::kV + 4 * vec) = pre_v[it];
+                const int g = tid + kThreads * it;   // kV == kK + 4 * kCodeVecs: keys then values, contiguous
+                *reinterpret_cast<u32x4 *>(buf + St::kK + 4 * g) = pre_kv[it];
             }
+            if (!ld_meta) return;
             // Position of this key in the per-lane order of the score tile: [tile][hh][4 g + r].
             const int tl = ld_key >> 5, r = ld_key & 31;
             const int slot = tl * 32 + ((r >> 2) & 1) * 16 + 4 * (r >> 3) + (r & 3);
@@ -460,18 +490,24 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 const uint16_t k_l = bf16_bits(ks - bf16_val(k_h));
                 cop.x = k_h | ((uint32_t)k_h << 16); cop.y = k_l | ((uint32_t)k_l << 16);
                 cop.z = 0u; cop.w = 0u;
-                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_b;
-                const uint16_t v_h = bf16_bits(pre_c);
-                const uint16_t v_l = bf16_bits(pre_c - bf16_val(v_h));
+                // Tokens outside the window get value scale 0: their probability is exactly 0, and whatever
+                // the storage holds there (it need not be initialised) must not turn that into a NaN.
+                const float vz = pre_valid ? pre_c : 0.0f;
+                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? pre_b : 0.0f;
+                const uint16_t v_h = bf16_bits(vz);
+                const uint16_t v_l = bf16_bits(vz - bf16_val(v_h));
                 reinterpret_cast<uint16_t *>(buf + St::kVzHi)[slot] = v_h;
                 reinterpret_cast<uint16_t *>(buf + St::kVzLo)[slot] = v_l;
+                // this half of the loader threads is two whole waves: one flag word each
+                const bool lo_any = __any(v_l != 0);
+                if (lane == 0) buf[St::kFlags + (wave & 1)] = lo_any ? 1u : 0u;
             }
             *reinterpret_cast<u32x4 *>(buf + St::kCop + (tl * 64 + ld_half * 32 + r) * 4) = cop;
         };
 
         // ---- pieces of one pipeline iteration
         // Scores of tile t (raw accumulators): constant-term MFMA, then high and low query parts.
-        auto score_tile = [&](int t, f32x16 (&sn)[2]) {
+        auto score_tile = [&](int t, f32x16 (&sn)[kRB]) {
             const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
             const int tl = t & 3;
             uint32_t kw[WPL];
@@ -487,8 +523,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            sn[0] = mfma_bf16(cop, rowop[0], zero);
-            sn[1] = mfma_bf16(cop, rowop[1], zero);
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_bf16(cop, rowop[rb], zero);
             // The low parts of q~ stay in LDS: the offset is made opaque so that the loads are issued per
             // tile instead of being hoisted into registers that do not exist.
             uint32_t off = lo_off;
@@ -497,16 +533,17 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
                 const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
-                const u32x4 lo0 = *reinterpret_cast<const u32x4 *>(qlo + 8 * SLAB);
-                const u32x4 lo1 = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * SLAB);
-                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
-                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
-                sn[0] = mfma_f16(kop, lo0, sn[0]);
-                sn[1] = mfma_f16(kop, lo1, sn[1]);
+                u32x4 lo[kRB];
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, lo[rb], sn[rb]);
             });
         };
         // e = scale_i * raw - reference; returns the tile maximum of e per row block.
-        auto finalize_tile = [&](int t, const f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2]) {
+        auto finalize_tile = [&](int t, const f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB]) {
             const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
             const float *ks = reinterpret_cast<const float *>(buf + St::kKScale) + (t & 3) * 32 + hh * 16;
             float k_scale[16];
@@ -516,7 +553,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
             }
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(k_scale[v], sn[rb][v], -m_ref[rb]);
                 float mx = fmaxf(e[rb][0], e[rb][1]);
@@ -526,7 +563,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             }
         };
         // p = 2^e, partial sums, p' = p * value-scale rounded to bf16 (B operands), tau.
-        auto exp_tile = [&](int t, const float (&e)[2][16], u32x4 (&pop)[2][2]) {
+        auto exp_tile = [&](int t, const float (&e)[kRB][16], u32x4 (&pop)[kRB][2]) {
             const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
             const int pos = (t & 3) * 32 + hh * 16;
             const float *vsp = reinterpret_cast<const float *>(buf + St::kVScale) + pos;
@@ -546,7 +583,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 zl[0] = l0.x; zl[1] = l0.y; zl[2] = l0.z; zl[3] = l0.w; zl[4] = l1.x; zl[5] = l1.y; zl[6] = l1.z; zl[7] = l1.w;
             }
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
                 float lsum = 0.0f, tacc = 0.0f;
                 uint32_t pw[8];
 #pragma unroll
@@ -565,7 +602,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             }
         };
         // O^T += V^T P^T on raw codes.
-        auto pv_tile = [&](int t, const u32x4 (&pop)[2][2]) {
+        auto pv_tile = [&](int t, const u32x4 (&pop)[kRB][2]) {
             const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
             uint32_t vw[WPL];
             {
@@ -580,10 +617,10 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 constexpr int B = decltype(b_)::value;
                 const u32x4 v0 = value_operand<BITS, B, 0>(vw, uc);
                 const u32x4 v1 = value_operand<BITS, B, 1>(vw, uc);
-                o[B][0] = mfma_bf16(v0, pop[0][0], o[B][0]);
-                o[B][1] = mfma_bf16(v0, pop[1][0], o[B][1]);
-                o[B][0] = mfma_bf16(v1, pop[0][1], o[B][0]);
-                o[B][1] = mfma_bf16(v1, pop[1][1], o[B][1]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(v0, pop[rb][0], o[B][rb]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(v1, pop[rb][1], o[B][rb]);
             });
         };
         // One steady-state iteration, interleaved by hand: the score MFMAs of tile t+1 (4 per key slab)
@@ -606,8 +643,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             }
             pf.cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
         };
-        auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[2], float (&e)[2][16], float (&tmax)[2],
-                                   u32x4 (&pop)[2][2]) {
+        auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
+                                   u32x4 (&pop)[kRB][2], uint32_t &lo_flag) {
             const uint32_t *bufn = lds + (((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
             const uint32_t *bufc = lds + ((t >> 2) % kBuffers) * St::kWords;         // holds tile t
             const int tln = (t + 1) & 3, tlc = t & 3;
@@ -622,49 +659,47 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     v_scale[4 * g] = c.x; v_scale[4 * g + 1] = c.y; v_scale[4 * g + 2] = c.z; v_scale[4 * g + 3] = c.w;
                 }
             }
-            uint32_t zh[8], zl[8];
+            uint32_t zh[8];
             {
                 const u32x4 h0 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzHi + pos / 2);
                 const u32x4 h1 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzHi + pos / 2 + 4);
-                const u32x4 l0 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzLo + pos / 2);
-                const u32x4 l1 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzLo + pos / 2 + 4);
                 zh[0] = h0.x; zh[1] = h0.y; zh[2] = h0.z; zh[3] = h0.w; zh[4] = h1.x; zh[5] = h1.y; zh[6] = h1.z; zh[7] = h1.w;
-                zl[0] = l0.x; zl[1] = l0.y; zl[2] = l0.z; zl[3] = l0.w; zl[4] = l1.x; zl[5] = l1.y; zl[6] = l1.z; zl[7] = l1.w;
             }
+            const u32x2 lo_flags = *reinterpret_cast<const u32x2 *>(bufc + St::kFlags);
             uint32_t off = lo_off;
             asm volatile("" : "+v"(off));
             const uint32_t *qlo = q_stage + off;
-            u32x4 lo_cur[2], lo_nxt[2];
-            lo_cur[0] = *reinterpret_cast<const u32x4 *>(qlo);
-            lo_cur[1] = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords);
+            u32x4 lo_cur[kRB], lo_nxt[kRB];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords);
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            sn[0] = mfma_bf16(pf.cop, rowop[0], zero);
-            sn[1] = mfma_bf16(pf.cop, rowop[1], zero);
-            float lsum[2] = {0.0f, 0.0f}, tacc[2] = {0.0f, 0.0f};
-            uint32_t pw[2][8];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_bf16(pf.cop, rowop[rb], zero);
+            float lsum[kRB] = {}, tacc[kRB] = {};
+            uint32_t pw[kRB][8];
             uint32_t vw[WPL];
             float k_scale[16];
             auto exp_chunk = [&](auto c_) {
-                constexpr int C = decltype(c_)::value;
-                constexpr int RB = C / 4, I0 = 2 * (C % 4);
+                constexpr int C = decltype(c_)::value;   // one eighth of the tile: kRB probability words
+                constexpr int RB = (C * kRB) / 8, I0 = (C * kRB) % 8;
 #pragma unroll
-                for (int i = I0; i < I0 + 2; ++i) {
+                for (int i = I0; i < I0 + kRB; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
                     const float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
                     lsum[RB] += p0 + p1;
                     pw[RB][i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
                     tacc[RB] = dot2_bf16(pw[RB][i], zh[i], tacc[RB]);
-                    tacc[RB] = dot2_bf16(pw[RB][i], zl[i], tacc[RB]);
                 }
             };
             KVQ_CHUNK_FENCE();
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
                 if constexpr (SLAB < 7) {   // next slab's low query parts
-                    lo_nxt[0] = *reinterpret_cast<const u32x4 *>(qlo + 8 * (SLAB + 1));
-                    lo_nxt[1] = *reinterpret_cast<const u32x4 *>(qlo + 32 * kQRowWords + 8 * (SLAB + 1));
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb)
+                        lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * (SLAB + 1));
                 }
                 if constexpr (SLAB == 5) {  // value codes and key scales for the second half of the iteration
                     const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
@@ -681,43 +716,64 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     }
                 }
                 const u32x4 kop = key_operand<BITS, SLAB>(pf.kw, uc);
-                sn[0] = mfma_f16(kop, qop[0][SLAB], sn[0]);
-                sn[1] = mfma_f16(kop, qop[1][SLAB], sn[1]);
-                sn[0] = mfma_f16(kop, lo_cur[0], sn[0]);
-                sn[1] = mfma_f16(kop, lo_cur[1], sn[1]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, lo_cur[rb], sn[rb]);
                 if constexpr (SLAB >= 1) exp_chunk(IntC<SLAB - 1>{});
-                lo_cur[0] = lo_nxt[0];
-                lo_cur[1] = lo_nxt[1];
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
                 KVQ_CHUNK_FENCE();
             });
             exp_chunk(IntC<7>{});
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
                 l_s[rb] += lsum[rb];
                 tau[rb] += tacc[rb];
                 pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
                 pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
             }
+            lo_flag = lo_flags.x | lo_flags.y;
             // key codes of the tile after next (its stage has been opened at the top of this iteration)
             prefetch_keys(t + 2, pf);
-            float mx[2] = {-INFINITY, -INFINITY};
+            float mx[kRB];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
             static_for<4>([&](auto b_) {
                 constexpr int B = decltype(b_)::value;
                 const u32x4 v0 = value_operand<BITS, B, 0>(vw, uc);
                 const u32x4 v1 = value_operand<BITS, B, 1>(vw, uc);
-                o[B][0] = mfma_bf16(v0, pop[0][0], o[B][0]);
-                o[B][1] = mfma_bf16(v0, pop[1][0], o[B][1]);
-                o[B][0] = mfma_bf16(v1, pop[0][1], o[B][0]);
-                o[B][1] = mfma_bf16(v1, pop[1][1], o[B][1]);
-                constexpr int RB = B / 2, V0 = 8 * (B % 2);
 #pragma unroll
-                for (int v = V0; v < V0 + 8; ++v) e[RB][v] = fmaf(k_scale[v], sn[RB][v], -m_ref[RB]);
+                for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(v0, pop[rb][0], o[B][rb]);
 #pragma unroll
-                for (int v = V0; v < V0 + 8; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
+                for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(v1, pop[rb][1], o[B][rb]);
+                constexpr int RB = (B * 4 * kRB) / 16, V0 = (B * 4 * kRB) % 16;   // one quarter of the tile
+#pragma unroll
+                for (int v = V0; v < V0 + 4 * kRB; ++v) e[RB][v] = fmaf(k_scale[v], sn[RB][v], -m_ref[RB]);
+#pragma unroll
+                for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
                 KVQ_CHUNK_FENCE();
             });
-            tmax[0] = max_halves(mx[0]);
-            tmax[1] = max_halves(mx[1]);
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(mx[rb]);
+        };
+        // Zero-points whose OFFSET + z needs a second bf16 piece (magnitude above 256) are rare.  The loader
+        // flags the stages that hold one; the fast loop only carries the flag and is left after such a tile,
+        // whose probabilities (still in pop) then meet the low parts here.
+        auto add_low_zero_points = [&](int t, const u32x4 (&pop)[kRB][2]) {
+            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const int pos = (t & 3) * 32 + hh * 16;
+            const u32x4 l0 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2);
+            const u32x4 l1 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2 + 4);
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) {
+                float tl = 0.0f;
+                tl = dot2_bf16(pop[rb][0].x, l0.x, tl); tl = dot2_bf16(pop[rb][0].y, l0.y, tl);
+                tl = dot2_bf16(pop[rb][0].z, l0.z, tl); tl = dot2_bf16(pop[rb][0].w, l0.w, tl);
+                tl = dot2_bf16(pop[rb][1].x, l1.x, tl); tl = dot2_bf16(pop[rb][1].y, l1.y, tl);
+                tl = dot2_bf16(pop[rb][1].z, l1.z, tl); tl = dot2_bf16(pop[rb][1].w, l1.w, tl);
+                tau[rb] += tl;
+            }
         };
         // A stage becomes visible one tile before its first tile is scored.
         auto open_stage = [&](int stage) {
@@ -728,9 +784,9 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
 
         prefetch(0);
         open_stage(0);
-        f32x16 sn[2];
-        float e[2][16], tmax[2];
-        u32x4 pop[2][2];
+        f32x16 sn[kRB];
+        float e[kRB][16], tmax[kRB];
+        u32x4 pop[kRB][2];
         score_tile(0, sn);
         finalize_tile(0, sn, e, tmax);
         if (n_tiles > 4) open_stage(1);   // stages are opened two tiles before their first tile is scored
@@ -738,7 +794,12 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         prefetch_keys(1, pf);
         int t = 0;
         bool done = false;
+        uint32_t lo_flag = 0u;   // nonzero: tile t-1 still owes tau its low zero-point parts
         while (!done) {
+            if (__builtin_amdgcn_readfirstlane(lo_flag) != 0u) {
+                add_low_zero_points(t - 1, pop);
+                lo_flag = 0u;
+            }
             move_reference(e, tmax);
             // fast loop: nothing in here touches the accumulators except the MFMAs
             for (;;) {
@@ -749,16 +810,16 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     break;
                 }
                 if (((t + 2) & 3) == 0 && t + 2 >= 8) open_stage((t + 2) >> 2);
-                fused_iteration(t, pf, sn, e, tmax, pop);
+                fused_iteration(t, pf, sn, e, tmax, pop, lo_flag);
                 ++t;
-                if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
+                if (__any(over_threshold(tmax) || lo_flag != 0u)) break;
             }
         }
 
         // ---- leave the rotated basis: O <- Hn^T (O_rot - tau 1).  Channel index of register
         // (b, v) in lane half hh: c = 32 b + 8 (v >> 2) + 4 hh + (v & 3).
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
             for (int h = 1; h < 16; h <<= 1) {   // channel bits 0, 1 (v bits 0, 1) and 3, 4 (v bits 2, 3)
 #pragma unroll
@@ -803,7 +864,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         const uint16_t *v_base = static_cast<const uint16_t *>(a.v_cur) + head_off;
         // B operands: the raw (unrotated, unscaled) bf16 queries.
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
             int64_t row = wave_row0 + 32 * rb + n;
             row = row < a.m ? row : a.m - 1;
             const uint16_t *src = q_base + row * a.stride_token + 8 * hh;
@@ -814,31 +875,33 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         __syncthreads();
         auto vt = [&](int i) -> uint16_t * { return reinterpret_cast<uint16_t *>(q_stage + (i & 1) * D * kVtRowWords); };
         const int n_tiles = (int)((a.n_cur + kTileTokens - 1) / kTileTokens);
-        u32x4 pre_vt[2];
-        const int ld_key = tid & 31, ld_oct = tid >> 5;  // octets ld_oct and ld_oct + 8
+        constexpr int kVtIters = 16 * 32 / kThreads;     // 16 channel octets x 32 tokens per tile
+        constexpr int kVtOcts = kThreads / 32;
+        u32x4 pre_vt[kVtIters];
+        const int ld_key = tid & 31, ld_oct = tid >> 5;  // octets ld_oct (+ kVtOcts)
         auto prefetch_v = [&](int tile) {
             int64_t key = (int64_t)tile * kTileTokens + ld_key;
             key = key < a.n_cur ? key : a.n_cur - 1;
             const uint16_t *src = v_base + key * a.stride_token;
-            pre_vt[0] = *reinterpret_cast<const u32x4 *>(src + 8 * ld_oct);
-            pre_vt[1] = *reinterpret_cast<const u32x4 *>(src + 8 * (ld_oct + 8));
+#pragma unroll
+            for (int it = 0; it < kVtIters; ++it) pre_vt[it] = *reinterpret_cast<const u32x4 *>(src + 8 * (ld_oct + kVtOcts * it));
         };
         auto commit_v = [&](uint16_t *buf) {
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
+            for (int it = 0; it < kVtIters; ++it) {
                 const uint32_t ws[4] = {pre_vt[it].x, pre_vt[it].y, pre_vt[it].z, pre_vt[it].w};
 #pragma unroll
                 for (int el = 0; el < 8; ++el) {
-                    const int ch = 8 * (ld_oct + 8 * it) + el;
+                    const int ch = 8 * (ld_oct + kVtOcts * it) + el;
                     const uint16_t val = (uint16_t)(el & 1 ? ws[el >> 1] >> 16 : ws[el >> 1] & 0xffffu);
                     buf[ch * (2 * kVtRowWords) + ld_key] = val;
                 }
             }
         };
-        auto score_cur = [&](int tile, float (&e)[2][16], float (&tmax)[2]) {
-            f32x16 s[2];
+        auto score_cur = [&](int tile, float (&e)[kRB][16], float (&tmax)[kRB]) {
+            f32x16 s[kRB];
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
+            for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[rb][v] = 0.0f;
             int64_t key = (int64_t)tile * kTileTokens + n;
@@ -849,13 +912,13 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
             for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 16 * slab);
 #pragma unroll
             for (int slab = 0; slab < 8; ++slab) {
-                s[0] = mfma_bf16(kop[slab], qop[0][slab], s[0]);
-                s[1] = mfma_bf16(kop[slab], qop[1][slab], s[1]);
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) s[rb] = mfma_bf16(kop[slab], qop[rb][slab], s[rb]);
             }
             const int64_t key_base = (int64_t)tile * kTileTokens + 4 * hh;
             const bool edge = (int64_t)(tile + 1) * kTileTokens > a.n_cur;
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(s[rb][v], c_log, -m_ref[rb]);
                 if (edge) {
@@ -871,10 +934,10 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 tmax[rb] = max_halves(mx);
             }
         };
-        auto pv_cur = [&](int tile, const float (&e)[2][16]) {
-            u32x4 pop[2][2];
+        auto pv_cur = [&](int tile, const float (&e)[kRB][16]) {
+            u32x4 pop[kRB][2];
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
                 float lsum = 0.0f;
                 uint32_t pw[8];
 #pragma unroll
@@ -899,8 +962,8 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                     const u32x2 hi = *reinterpret_cast<const u32x2 *>(rowp + 8 * sl + 4);
                     u32x4 vop;
                     vop.x = lo.x; vop.y = lo.y; vop.z = hi.x; vop.w = hi.y;
-                    o[b][0] = mfma_bf16(vop, pop[0][sl], o[b][0]);
-                    o[b][1] = mfma_bf16(vop, pop[1][sl], o[b][1]);
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) o[b][rb] = mfma_bf16(vop, pop[rb][sl], o[b][rb]);
                 }
             }
         };
@@ -908,7 +971,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
         prefetch_v(0);
         commit_v(vt(0));
         __syncthreads();
-        float e[2][16], tmax[2];
+        float e[kRB][16], tmax[kRB];
         int tile = 0;
         score_cur(0, e, tmax);
         bool done = false;
@@ -923,7 +986,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
                 if (!more) { done = true; break; }
                 ++tile;
                 score_cur(tile, e, tmax);
-                if (__any(tmax[0] > kRescaleThreshold || tmax[1] > kRescaleThreshold)) break;
+                if (__any(over_threshold(tmax))) break;
             }
         }
     }
@@ -931,7 +994,7 @@ __global__ __launch_bounds__(256, 1) void attention_mfma_kernel(AttentionArgs a,
     // ------------------------------------------------------------------------- epilogue ----
     uint16_t *out_base = static_cast<uint16_t *>(a.out) + head_off;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < kRB; ++rb) {
         const float ls = l_s[rb] + xhalf(l_s[rb]);
         const float lr = l_r[rb] + xhalf(l_r[rb]);
         const float inv = 1.0f / (ls + lr);
@@ -964,7 +1027,7 @@ template <int BITS, bool CORR> hipError_t launch(const AttentionArgs &a, hipStre
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR>), dim3((unsigned)blocks), dim3(256), lds_bytes<BITS>(), stream,
+    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
                        a, row_blocks);
     return hipGetLastError();
 }

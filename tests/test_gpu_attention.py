@@ -122,6 +122,35 @@ def test_softmax_scale_and_large_queries(P):
             P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "sigma=%g" % sigma)
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_large_zero_points(P, bits):
+    """Vectors that are a spike in channel 0 plus small noise rotate into a large offset with a small range,
+    so their zero-points reach several hundred: beyond one bf16 piece on the matrix-core path."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads = 2
+    n_cached, n_cur, m = 200, 64, 96
+
+    def spiky(x, noise):
+        x = x * np.float32(noise)
+        x[..., 0] += np.float32(2.0)
+        return wl.round_to_bf16(x)
+
+    k0, v0 = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    kc, vc = spiky(k0, 2e-3), spiky(v0, 2e-4)
+    cache = P.make_cache(w, 256, heads=heads)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    _, _, zeros = B.export_all(cache, 1)
+    assert float(zeros.abs().max()) > 300.0                      # the case this test is about
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.chunk_q(w, heads=range(heads))[:m]
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 1)
+    for fp32_kernel in (True, False):
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", fp32_kernel=fp32_kernel)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "large zero-points int%d" % bits)
+
+
 def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None):
     """Full-size GPU run as the benchmark launches it; oracle on sampled heads x sampled rows."""
     import oracle

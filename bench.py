@@ -27,6 +27,10 @@ import numpy as np
 
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/f16 matrix peak
 HBM_PEAK_GBS = 8000.0
+# HBM bytes of one attention launch on the Large workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
+# this program scaled by the same counters on a plain 1 GiB elementwise kernel (--calibration-copy):
+# 221,557 KiB x 2.000 + 50,258 KiB x 1.000 (profiles/attention_mfma_large_int2_counters.md).
+ATTENTION_TRAFFIC_BYTES_LARGE = 505.2e6
 
 
 def parse():
@@ -37,6 +41,10 @@ def parse():
     ap.add_argument("--workload", default="large", choices=["small", "mid", "large", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=8, help="heads (all query rows each) given to the CPU oracle")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="before the warmup, run a plain elementwise kernel over a 1 GiB buffer three times "
+                         "(dst = src + 1: reads 1 GiB, writes 1 GiB; outside the timed region): the yardstick "
+                         "for FETCH_SIZE / WRITE_SIZE counter runs")
     return ap.parse_args()
 
 
@@ -186,6 +194,13 @@ def main():
         if events:
             events[2].record()
 
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -249,7 +264,7 @@ def main():
             "peak": MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": att_tflops / MFMA_PEAK_TFLOPS,
-            "traffic": None,
+            "traffic": ATTENTION_TRAFFIC_BYTES_LARGE if w.name == "large" else None,
         },
     }
     if not args.no_cpu_baseline:

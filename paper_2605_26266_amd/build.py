@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkvq.so")
+MICROBENCH = os.path.join(HERE, "kvq_microbench")   # stand-alone issue-rate microbenchmarks
 
 # Packed-FP32 code generation is switched off for every device translation unit.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
@@ -45,8 +46,13 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    cmd = ["hipcc", *COMMON, os.path.join(CSRC, "kvq_microbench.hip"), "-o", MICROBENCH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for kvq_microbench.hip:\n" + r.stderr)
     if verbose:
         print("built", LIB)
+        print("built", MICROBENCH)
     return LIB
 
 

@@ -1,0 +1,219 @@
+// Issue-rate microbenchmarks for gfx950, the yardsticks the attention and quantize kernels are read
+// against: sustained MFMA rate, what vector instructions cost next to MFMAs in one in-order wave (and
+// with two waves per SIMD), LDS read rate by access width, and a plain HBM copy of the size one
+// quantize-append call moves.  Stand-alone program; every loop has a fixed trip count.
+//
+//   kvq_microbench            prints one table per experiment
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+#define CHECK(x)                                                                        \
+    do {                                                                                \
+        hipError_t e_ = (x);                                                            \
+        if (e_ != hipSuccess) {                                                         \
+            fprintf(stderr, "%s:%d: %s\n", __FILE__, __LINE__, hipGetErrorString(e_));  \
+            exit(1);                                                                    \
+        }                                                                               \
+    } while (0)
+
+constexpr int kBlocks = 256;   // one workgroup per compute unit
+constexpr int kIters = 2000;
+
+enum Op { kFma, kMul, kAndOr, kShift, kCvtPk, kDot2, kExp2, kMax3 };
+
+// W waves per SIMD; each wave runs kIters x 8 steps of (one 32x32x16 MFMA on one of CH accumulators,
+// then NV independent vector instructions of kind OP).
+template <int W, int CH, int NV, Op OP>
+__global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t mask, uint32_t base)
+{
+    f16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (_Float16)(threadIdx.x * 0.001f + i);
+        b[i] = (_Float16)(i * 0.5f);
+    }
+    f32x16 c[8];
+    for (int j = 0; j < 8; ++j)
+        for (int v = 0; v < 16; ++v) c[j][v] = 0.0f;
+    float x[16], y[16];
+    uint32_t u[16];
+    for (int i = 0; i < 16; ++i) {
+        x[i] = threadIdx.x * 0.01f + i;
+        y[i] = 0.5f + 0.001f * i + threadIdx.x * 1.0e-6f;
+        u[i] = threadIdx.x * 7 + i;
+    }
+    const uint32_t bs = base + threadIdx.x;
+    for (int it = 0; it < kIters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (CH > 0) c[j % (CH > 0 ? CH : 1)] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c[j % (CH > 0 ? CH : 1)], 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int k = (j * NV + v) & 15, k1 = (k + 1) & 15;
+                if (OP == kFma) x[k] = __builtin_fmaf(x[k], y[k], y[k1]);
+                else if (OP == kMul) x[k] = x[k] * y[k];
+                else if (OP == kAndOr) { asm("" : "+v"(u[k]));  u[k] = (u[k] & mask) | bs; }   // opaque source: cannot be folded
+                else if (OP == kShift) { asm("" : "+v"(u[k]));  u[k] = u[k] >> 1; }
+                else if (OP == kCvtPk) {
+                    f32x2 f = {x[k], y[k]};
+                    u[k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+                    x[k] = __uint_as_float(u[k]);
+                } else if (OP == kDot2)
+                    x[k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u[k]), __builtin_bit_cast(bf16x2, u[k1]), x[k], false);
+                else if (OP == kExp2) x[k] = __builtin_amdgcn_exp2f(x[k]);
+                else if (OP == kMax3) y[k] = __builtin_fmaxf(__builtin_fmaxf(y[k], x[k]), x[k1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = 0.0f;
+    for (int j = 0; j < 8; ++j)
+        for (int v = 0; v < 16; ++v) s += c[j][v];
+    for (int i = 0; i < 16; ++i) s += x[i] + y[i] + (float)u[i];
+    out[blockIdx.x * 256 * W + threadIdx.x] = s;
+}
+
+template <typename F> float time_ms(F &&launch)
+{
+    hipEvent_t e0, e1;
+    CHECK(hipEventCreate(&e0));
+    CHECK(hipEventCreate(&e1));
+    launch();   // warm-up
+    CHECK(hipDeviceSynchronize());
+    CHECK(hipEventRecord(e0));
+    launch();
+    CHECK(hipEventRecord(e1));
+    CHECK(hipEventSynchronize(e1));
+    float ms = 0.0f;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    CHECK(hipGetLastError());
+    CHECK(hipEventDestroy(e0));
+    CHECK(hipEventDestroy(e1));
+    return ms;
+}
+
+// ns per step (one MFMA + NV instructions) and per SIMD: with W waves a SIMD completes W steps in that time.
+template <int W, int CH, int NV, Op OP> double step_ns(float *out)
+{
+    const float ms = time_ms([&] { mix_kernel<W, CH, NV, OP><<<kBlocks, 256 * W>>>(out, 0x03000300u, 0x44004400u); });
+    return ms * 1e6 / (kIters * 8.0) / W;
+}
+
+template <Op OP> void op_row(float *out, const char *name)
+{
+    const double a = step_ns<1, 4, 8, OP>(out), b = step_ns<1, 4, 16, OP>(out);
+    const double c = step_ns<2, 4, 8, OP>(out), d = step_ns<2, 4, 16, OP>(out);
+    printf("| %-12s | %6.2f | %6.2f | %5.2f | %6.2f | %6.2f | %5.2f |\n", name, a, b, (b - a) / 8, c, d, (d - c) / 8);
+}
+
+template <typename T> __global__ __launch_bounds__(512, 1) void lds_kernel(uint32_t *out, int iters)
+{
+    extern __shared__ u32x4 lds[];
+    for (int i = threadIdx.x; i < 8192; i += 512) lds[i] = u32x4{(uint32_t)i, 1u, 2u, 3u};
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const T *base = reinterpret_cast<const T *>(lds + (wave & 3) * 1024) + lane;
+    for (int it = 0; it < iters; ++it) {
+        T r[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) r[j] = base[64 * j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) asm volatile("" ::"v"(r[j]));
+        asm volatile("" : "+v"(base));
+    }
+    out[blockIdx.x * 512 + threadIdx.x] = 0u;
+}
+
+template <typename T> void lds_row(uint32_t *out, const char *name)
+{
+    const int iters = 4000;
+    CHECK(hipFuncSetAttribute((const void *)lds_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 8192 * 16));
+    const float ms = time_ms([&] { lds_kernel<T><<<kBlocks, 512, 8192 * 16>>>(out, iters); });
+    const double instr = (double)iters * 16 * 8;   // wave-instructions per compute unit
+    printf("| %-13s | %6.2f | %7.1f |\n", name, ms * 1e6 / instr, instr * 64 * sizeof(T) / (ms * 1e6));
+}
+
+__global__ void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+int main()
+{
+    float *out;
+    CHECK(hipMalloc(&out, (size_t)kBlocks * 512 * sizeof(float)));
+
+    printf("## MFMA only: ns per v_mfma_f32_32x32x16_f16 per SIMD (32768 flop each, 1024 SIMDs)\n\n");
+    printf("| waves/SIMD | accumulator chains | ns per MFMA | chip TFLOP/s |\n|---|---|---|---|\n");
+    {
+        const double r[5] = {step_ns<1, 1, 0, kFma>(out), step_ns<1, 2, 0, kFma>(out), step_ns<1, 4, 0, kFma>(out),
+                             step_ns<1, 8, 0, kFma>(out), step_ns<2, 4, 0, kFma>(out)};
+        const int w[5] = {1, 1, 1, 1, 2}, ch[5] = {1, 2, 4, 8, 4};
+        for (int i = 0; i < 5; ++i) printf("| %d | %d | %.2f | %.0f |\n", w[i], ch[i], r[i], 32768.0 / r[i] * 1024 / 1e3);
+    }
+
+    printf("\n## One MFMA followed by N independent v_fma_f32: ns per step per SIMD\n\n");
+    printf("| N | 1 wave/SIMD | 2 waves/SIMD |\n|---|---|---|\n");
+    printf("| 0 | %.2f | %.2f |\n", step_ns<1, 4, 0, kFma>(out), step_ns<2, 4, 0, kFma>(out));
+    printf("| 4 | %.2f | %.2f |\n", step_ns<1, 4, 4, kFma>(out), step_ns<2, 4, 4, kFma>(out));
+    printf("| 8 | %.2f | %.2f |\n", step_ns<1, 4, 8, kFma>(out), step_ns<2, 4, 8, kFma>(out));
+    printf("| 12 | %.2f | %.2f |\n", step_ns<1, 4, 12, kFma>(out), step_ns<2, 4, 12, kFma>(out));
+    printf("| 16 | %.2f | %.2f |\n", step_ns<1, 4, 16, kFma>(out), step_ns<2, 4, 16, kFma>(out));
+    printf("| 16, no MFMA | %.2f | %.2f |\n", step_ns<1, 0, 16, kFma>(out), step_ns<2, 0, 16, kFma>(out));
+
+    printf("\n## Marginal cost of one vector instruction next to MFMAs (step = 1 MFMA + N instr; ns per SIMD)\n\n");
+    printf("| instruction | 1w N=8 | 1w N=16 | 1w ns/instr | 2w N=8 | 2w N=16 | 2w ns/instr |\n|---|---|---|---|---|---|---|\n");
+    op_row<kFma>(out, "v_fma_f32");
+    op_row<kMul>(out, "v_mul_f32");
+    op_row<kAndOr>(out, "v_and_or_b32");
+    op_row<kShift>(out, "v_lshrrev_b32");
+    op_row<kCvtPk>(out, "v_cvt_pk_bf16");
+    op_row<kDot2>(out, "v_dot2_bf16");
+    op_row<kExp2>(out, "v_exp_f32");
+    op_row<kMax3>(out, "v_max3_f32");
+
+    printf("\n## LDS reads, 8 waves per compute unit, conflict-free: per wave-instruction and compute unit\n\n");
+    printf("| instruction | ns | bytes per ns |\n|---|---|---|\n");
+    lds_row<uint32_t>(reinterpret_cast<uint32_t *>(out), "ds_read_b32");
+    lds_row<u32x2>(reinterpret_cast<uint32_t *>(out), "ds_read_b64");
+    lds_row<u32x4>(reinterpret_cast<uint32_t *>(out), "ds_read_b128");
+
+    printf("\n## HBM copy of the bytes one quantize-append call moves at the large shape\n\n");
+    {
+        // 100.7 MB read + 15.7 MB written by the quantizer; a copy reads and writes n bytes each: n = 58.2 MB
+        const size_t bytes = 58200000 / 16 * 16, n = bytes / 16;
+        u32x4 *src, *dst;
+        CHECK(hipMalloc(&src, bytes));
+        CHECK(hipMalloc(&dst, bytes));
+        CHECK(hipMemset(src, 1, bytes));
+        float best = 1e30f;
+        for (int r = 0; r < 5; ++r) {
+            const float ms = time_ms([&] { copy_kernel<<<kBlocks * 16, 256>>>(src, dst, n); });
+            best = ms < best ? ms : best;
+        }
+        printf("copy of 2 x %.1f MB: %.1f us, %.2f TB/s\n", bytes / 1e6, best * 1e3, 2.0 * bytes / (best * 1e-3) / 1e12);
+        const size_t big = (size_t)1 << 30;
+        u32x4 *s2, *d2;
+        CHECK(hipMalloc(&s2, big));
+        CHECK(hipMalloc(&d2, big));
+        CHECK(hipMemset(s2, 1, big));
+        best = 1e30f;
+        for (int r = 0; r < 3; ++r) {
+            const float ms = time_ms([&] { copy_kernel<<<kBlocks * 16, 256>>>(s2, d2, big / 16); });
+            best = ms < best ? ms : best;
+        }
+        printf("copy of 2 x 1 GiB: %.1f us, %.2f TB/s\n", best * 1e3, 2.0 * big / (best * 1e-3) / 1e12);
+        CHECK(hipFree(src)); CHECK(hipFree(dst)); CHECK(hipFree(s2)); CHECK(hipFree(d2));
+    }
+    CHECK(hipFree(out));
+    return 0;
+}

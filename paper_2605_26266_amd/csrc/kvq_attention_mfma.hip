@@ -12,27 +12,27 @@
 //
 // Cached keys/values (Alg. 1 of the paper, cached block).  Packed tiles (see kvq_internal.h) are
 // staged through LDS 128 keys at a time (four buffers, one barrier per stage).  A lane pulls its 16
-// or 32 bytes of codes and turns every word into MFMA operand registers with one shift and one
-// and-or per register: the code lands in the top mantissa bits of a 16-bit float whose exponent makes
-// the value OFFSET + code (4 + code for 2 bits, 16 + code for 4 bits).  Key codes and the rotated
+// or 32 bytes of codes and turns every word into MFMA operand registers with an and-or per register
+// and a shift per one to three registers: the code lands in mantissa bits of a 16-bit float whose
+// exponent makes the value BASE + weight * code (see "Unpacking" below).  Key codes and the rotated
 // query use f16 (same MFMA rate as bf16, three more significant bits; codes are exact either way) and
 // the query is carried as a high + low f16 pair; value codes and probabilities use bf16 (its range is
 // needed for p * value-scale).  Per-token scale and zero-point never touch the operands: with one
 // (scale, zero) per token
-//     s_mi = scale_i * ( q~_m . (OFFSET + code_i)  -  (OFFSET + z_i) * sum_c q~_mc  -  scale_i * nu'_m )
-// where q~ already carries softmax_scale * log2(e) / sqrt(d) and nu'_m = softmax_scale^2 * log2(e) *
-// ||q_m||^2 / 24 is the Taylor correction b (Eq. 13 / Eq. 15 with one group) in units of scale_i^2,
-// from ||q_m||^2 computed once per row.  The two rank-one terms ride on the matrix cores as well: the
-// loader turns (zero, scale, window mask) of each key into one more 16-wide A operand, the row
-// constants (sum of q~, nu') form its B operand, split into bf16 pieces that add up to fp32 accuracy.
-// The correction therefore costs no vector instruction at all; what is left per score is one fused
-// multiply-add (scale, minus the reference maximum), the exponential and the P*V bookkeeping.
-// On the value side the value scale is folded into the probability before it is rounded to bf16, and
-// the zero-point/OFFSET term is a per-row scalar tau_m = sum_i p'_mi (OFFSET + z_i), accumulated from
-// the rounded probabilities (dot2 on bf16 pairs) so that it cancels exactly.  The cached part of O
-// lives in the rotated basis; when the cached keys are done the accumulators are rotated back in
-// registers (six butterfly stages inside the lane, one between the lane halves) and the loop continues
-// with the current chunk in the original basis.
+//     s_mi = scale_i * ( q~_m . (BASE + code_i)  -  z_i * sum_c q~_mc  -  BASE * W_m  -  scale_i * nu'_m )
+// where q~ already carries softmax_scale * log2(e) / sqrt(d), W_m is the sum of the operand values of
+// the row, and nu'_m = softmax_scale^2 * log2(e) * ||q_m||^2 / 24 is the Taylor correction b (Eq. 13 /
+// Eq. 15 with one group) in units of scale_i^2, from ||q_m||^2 computed once per row.  The rank-one
+// terms ride on the matrix cores as well: the loader turns (zero, scale, window mask) of each key into
+// one more 16-wide A operand, the row constants form its B operand, split into bf16 pieces that add up
+// to fp32 accuracy.  The correction therefore costs no vector instruction at all; what is left per
+// score is one fused multiply-add (scale, minus the reference maximum), the exponential and the P*V
+// bookkeeping.  On the value side the value scale is folded into the probability before it is rounded
+// to bf16, and the zero-point/BASE term is a per-row scalar tau_m = sum_i p'_mi (BASE + z_i),
+// accumulated from the rounded probabilities (dot2 on bf16 pairs) so that it cancels exactly.  The
+// cached part of O lives in the rotated basis; when the cached keys are done the accumulators are
+// rotated back in registers (six butterfly stages inside the lane, one between the lane halves) and
+// the loop continues with the current chunk in the original basis.
 //
 // Software pipeline.  One iteration issues the score MFMAs of tile t+1 next to the exponentials of
 // tile t, then the P*V MFMAs of tile t next to the scaling of the scores of tile t+1, so that a single
@@ -99,7 +99,7 @@ template <int BITS> struct Stage {
 template <int BITS> constexpr size_t lds_bytes()
 {
     // stage buffers | per-wave low parts of q~ (also staging for the query prep and the V^T tiles) | row scalars
-    return sizeof(uint32_t) * (kBuffers * Stage<BITS>::kWords + kRowsPerBlock * kQRowWords + 2 * kRowsPerBlock);
+    return sizeof(uint32_t) * (kBuffers * Stage<BITS>::kWords + kRowsPerBlock * kQRowWords + 4 * kRowsPerBlock);
 }
 
 __device__ inline f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
@@ -132,24 +132,51 @@ __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
 }
 
-// Unpack constants.  They are passed through an empty asm once per kernel so that the compiler
-// keeps them in registers (mask in a scalar, base in a vector register) and selects v_and_or_b32
-// for (x & mask) | base; the instruction itself is emitted by the compiler, which matters because
-// it must know about the vector write in front of the matrix instruction that reads the register.
+// Unpacking.  A packed word holds 16 (2-bit) or 8 (4-bit) codes, in pairs `bits` apart in the low and
+// the high half-word; register J of the word is the pair at bit 2J (4J) of each half.  An operand
+// register is made as (shifted word & mask) | base: the code lands in mantissa bits of a 16-bit float
+// whose exponent is the base, i.e. the value is BASE + weight * code.
+//
+// 2-bit codes: three adjacent pairs are cut out of the same shifted word, at mantissa positions two bits
+// apart, so their weights are 1, 1/4 and 1/16 (class g = 0, 1, 2 of register J is 2 - J mod 3).  The
+// other operand of the MFMA carries the inverse weight, which is exact: for keys the query channel is
+// multiplied by 4^g, for values the probability (through the value scale) is.  This saves the shift of
+// five registers in eight.  Key values are 4 + code * 4^-g (f16), value values 8 + code * 4^-g (bf16).
+// 4-bit codes: one pair per shift, 16 + code on both sides.
+//
+// The constants are passed through an empty asm once per kernel so that the compiler keeps them in
+// registers (masks in scalars, bases in vector registers) and selects v_and_or_b32; the instruction
+// itself is emitted by the compiler, which matters because it must know about the vector write in
+// front of the matrix instruction that reads the register.
 struct UnpackConsts {
-    uint32_t kmask, kbase, vmask, vbase;
+    uint32_t kmask[3], kbase, vmask[3], vbase;
 };
 template <int BITS> __device__ inline UnpackConsts make_unpack_consts()
 {
     UnpackConsts c;
-    c.kmask = BITS == 2 ? 0x03000300u : 0x03c003c0u;
-    c.kbase = BITS == 2 ? 0x44004400u : 0x4c004c00u;
-    c.vmask = BITS == 2 ? 0x00600060u : 0x00780078u;
-    c.vbase = BITS == 2 ? 0x40804080u : 0x41804180u;
-    asm volatile("" : "+s"(c.kmask), "+s"(c.vmask));
+    if constexpr (BITS == 2) {
+        c.kmask[0] = 0x03000300u; c.kmask[1] = 0x00c000c0u; c.kmask[2] = 0x00300030u;
+        c.kbase = 0x44004400u;   // f16 4.0
+        c.vmask[0] = 0x00300030u; c.vmask[1] = 0x000c000cu; c.vmask[2] = 0x00030003u;
+        c.vbase = 0x41004100u;   // bf16 8.0
+    } else {
+        c.kmask[0] = c.kmask[1] = c.kmask[2] = 0x03c003c0u;
+        c.kbase = 0x4c004c00u;   // f16 16.0
+        c.vmask[0] = c.vmask[1] = c.vmask[2] = 0x00780078u;
+        c.vbase = 0x41804180u;   // bf16 16.0
+    }
+#pragma unroll
+    for (int g = 0; g < 3; ++g) asm volatile("" : "+s"(c.kmask[g]), "+s"(c.vmask[g]));
     asm volatile("" : "+v"(c.kbase), "+v"(c.vbase));
     return c;
 }
+// Offsets of the operand values and weight class of register J (see above).
+template <int BITS> struct Unpack {
+    static constexpr float kKeyBase = BITS == 2 ? 4.0f : 16.0f;
+    static constexpr float kValueBase = BITS == 2 ? 8.0f : 16.0f;
+    static constexpr float kStoredOffset = BITS == 2 ? 4.0f : 16.0f;   // the cache stores zero + this
+    __host__ __device__ static constexpr int weight_class(int j) { return BITS == 2 ? 2 - j % 3 : 0; }
+};
 
 template <int SH> __device__ inline uint32_t shift(uint32_t w)
 {
@@ -157,17 +184,29 @@ template <int SH> __device__ inline uint32_t shift(uint32_t w)
     else return w >> (-SH);
 }
 
-// Register J of a packed word -> two f16 values OFFSET + code (keys).
+// Register J of a packed word -> two f16 key values.
 template <int BITS, int J> __device__ inline uint32_t key_pair(uint32_t w, const UnpackConsts &c)
 {
-    if constexpr (BITS == 2) return (shift<8 - 2 * J>(w) & c.kmask) | c.kbase;
-    else return (shift<6 - 4 * J>(w) & c.kmask) | c.kbase;
+    if constexpr (BITS == 2) {
+        constexpr int G = Unpack<2>::weight_class(J);          // pair lands at mantissa bits 9:8, 7:6 or 5:4
+        constexpr int SH = J < 3 ? 4 : J < 6 ? -2 : -8;        // shared by the registers of one group
+        static_assert(2 * J + SH == 8 - 2 * G, "key pair position");
+        return (shift<SH>(w) & c.kmask[G]) | c.kbase;
+    } else {
+        return (shift<6 - 4 * J>(w) & c.kmask[0]) | c.kbase;
+    }
 }
-// Register J of a packed word -> two bf16 values OFFSET + code (values).
+// Register J of a packed word -> two bf16 value values.
 template <int BITS, int J> __device__ inline uint32_t value_pair(uint32_t w, const UnpackConsts &c)
 {
-    if constexpr (BITS == 2) return (shift<5 - 2 * J>(w) & c.vmask) | c.vbase;
-    else return (shift<3 - 4 * J>(w) & c.vmask) | c.vbase;
+    if constexpr (BITS == 2) {
+        constexpr int G = Unpack<2>::weight_class(J);          // pair lands at mantissa bits 5:4, 3:2 or 1:0
+        constexpr int SH = J < 3 ? 0 : J < 6 ? -6 : -12;
+        static_assert(2 * J + SH == 4 - 2 * G, "value pair position");
+        return (shift<SH>(w) & c.vmask[G]) | c.vbase;
+    } else {
+        return (shift<3 - 4 * J>(w) & c.vmask[0]) | c.vbase;
+    }
 }
 
 // A operand of 16-wide slab SLAB of a key tile, from the lane's WPL code words.
@@ -201,6 +240,15 @@ template <int BITS, int BLK, int S> __device__ inline u32x4 value_operand(const 
         r.z = value_pair<4, 2>(word, c); r.w = value_pair<4, 3>(word, c);
     }
     return r;
+}
+// Weight class of query channel c (keys) and of the key held in score register v (values).
+template <int BITS> __host__ __device__ constexpr int key_channel_class(int c)
+{
+    return Unpack<BITS>::weight_class(BITS == 2 ? 4 * ((c >> 4) & 1) + ((c >> 1) & 3) : 0);
+}
+template <int BITS> __host__ __device__ constexpr int value_register_class(int v)
+{
+    return Unpack<BITS>::weight_class(BITS == 2 ? (v >> 1) : 0);
 }
 
 __device__ inline float xhalf(float v) { return __shfl_xor(v, 32); }
@@ -297,9 +345,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 x[i] = ppart ? other - x[i] : x[i] + other;
             }
         }
+        // Channel c of the operand carries 4^g(c) (the inverse of the weight its key codes are unpacked with).
         const float cq = c_log * 0.088388347648318f;
 #pragma unroll
-        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq;
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (float)(1 << (2 * key_channel_class<BITS>(i)));
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
         uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
@@ -318,7 +367,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             for (int s = 0; s < 8; ++s)
                 qop[rb][s] = *reinterpret_cast<const u32x4 *>(hsrc + 32 * rb * kQRowWords + 8 * s);
         __syncthreads();
-        float ssum = 0.0f;
+        float ssum = 0.0f, ssum_w = 0.0f;   // sum of q~ (true scale), sum of the weighted operand values
 #pragma unroll
         for (int i = 0; i < kPrepCh / 8; ++i) {
             uint32_t lo[4];
@@ -328,39 +377,52 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const uint32_t hi = pack_f16(v0, v1);
                 const float h0 = f16_lo(hi), h1 = f16_hi(hi);
                 lo[j] = pack_f16(v0 - h0, v1 - h1);
-                ssum += (h0 + f16_lo(lo[j])) + (h1 + f16_hi(lo[j]));
+                const float pair = (h0 + f16_lo(lo[j])) + (h1 + f16_hi(lo[j]));   // both channels share a class
+                ssum_w += pair;
+                ssum += pair * (1.0f / (float)(1 << (2 * key_channel_class<BITS>(8 * i + 2 * j))));
             }
             u32x4 w;
             w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
             *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
         }
-        if constexpr (kPrepLanes == 2) ssum += __shfl_xor(ssum, 1);
+        if constexpr (kPrepLanes == 2) {
+            ssum += __shfl_xor(ssum, 1);
+            ssum_w += __shfl_xor(ssum_w, 1);
+        }
         if (ppart == 0) {
-            row_scal[2 * prow] = ssum;
-            row_scal[2 * prow + 1] = CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
+            row_scal[4 * prow] = ssum;
+            row_scal[4 * prow + 1] = ssum_w;
+            row_scal[4 * prow + 2] = CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
         }
     }
     __syncthreads();
-    // B operand of the constant-term MFMA, per 32-row block.  Lane half 0 multiplies the key's
-    // -(OFFSET + zero) pieces and the mask bias, lane half 1 the key's scale pieces:
-    //   hh = 0: [S_h, S_m, S_l, S_h, S_m, S_l, 1, 0]   S  = sum_c q~_c  in three bf16 pieces
-    //   hh = 1: [N_h, N_l, N_h, N_l, 0, 0, 0, 0]       N  = -nu'        in two bf16 pieces
+    // B operand of the constant-term MFMA, per 32-row block.  The raw score is sum_c (q~_c 4^g) (BASE +
+    // 4^-g code_c) = q~ . code + BASE * W with W the sum of the weighted operand values, so what has to
+    // come off is z * S + BASE * W (S = sum_c q~_c).  Lane half 0 multiplies the key's -z pieces and the
+    // mask bias, lane half 1 the key's scale pieces and the constant -BASE:
+    //   hh = 0: [S_h, S_m, S_l, S_h, S_m, S_l, 1, 0]     S in three bf16 pieces
+    //   hh = 1: [N_h, N_l, N_h, N_l, W_h, W_m, W_l, 0]   N = -nu' in two pieces, W in three
     u32x4 rowop[kRB];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
-        const float ssum = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n)];
-        const float nnu = row_scal[2 * (wave * kRowsPerWave + 32 * rb + n) + 1];
+        const float *rs = row_scal + 4 * (wave * kRowsPerWave + 32 * rb + n);
+        const float ssum = rs[0], wsum = rs[1], nnu = rs[2];
         const uint16_t s_h = bf16_bits(ssum);
         const float r1 = ssum - bf16_val(s_h);
         const uint16_t s_m = bf16_bits(r1);
         const uint16_t s_l = bf16_bits(r1 - bf16_val(s_m));
+        const uint16_t w_h = bf16_bits(wsum);
+        const float r2 = wsum - bf16_val(w_h);
+        const uint16_t w_m = bf16_bits(r2);
+        const uint16_t w_l = bf16_bits(r2 - bf16_val(w_m));
         const uint16_t n_h = bf16_bits(nnu);
         const uint16_t n_l = bf16_bits(nnu - bf16_val(n_h));
         const uint32_t one = 0x3f80u;
         u32x4 w0, w1;
         w0.x = s_h | ((uint32_t)s_m << 16); w0.y = s_l | ((uint32_t)s_h << 16);
         w0.z = s_m | ((uint32_t)s_l << 16); w0.w = one;
-        w1.x = n_h | ((uint32_t)n_l << 16); w1.y = w1.x; w1.z = 0u; w1.w = 0u;
+        w1.x = n_h | ((uint32_t)n_l << 16); w1.y = w1.x;
+        w1.z = w_h | ((uint32_t)w_m << 16); w1.w = w_l;
         rowop[rb] = hh ? w1 : w0;
     }
     const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
@@ -476,8 +538,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             const int slot = tl * 32 + ((r >> 2) & 1) * 16 + 4 * (r >> 3) + (r & 3);
             u32x4 cop;
             if (ld_half == 0) {
-                // -(OFFSET + zero) in two bf16 pieces (exact for |.| < 2^16), and the window mask.
-                const float nz = pre_valid ? pre_a : 0.0f;
+                // -zero in two bf16 pieces (exact for |.| < 2^16), and the window mask.
+                const float nz = pre_valid ? pre_a + Unpack<BITS>::kStoredOffset : 0.0f;
                 const uint16_t z_h = bf16_bits(nz);
                 const uint16_t z_l = bf16_bits(nz - bf16_val(z_h));
                 cop.x = z_h | ((uint32_t)z_h << 16); cop.y = z_h | ((uint32_t)z_l << 16);
@@ -488,12 +550,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const float ks = pre_valid ? pre_a : 0.0f;
                 const uint16_t k_h = bf16_bits(ks);
                 const uint16_t k_l = bf16_bits(ks - bf16_val(k_h));
+                const uint32_t nb = pre_valid ? (uint32_t)bf16_bits(-Unpack<BITS>::kKeyBase) : 0u;   // exact
                 cop.x = k_h | ((uint32_t)k_h << 16); cop.y = k_l | ((uint32_t)k_l << 16);
-                cop.z = 0u; cop.w = 0u;
+                cop.z = nb | (nb << 16); cop.w = nb;
                 // Tokens outside the window get value scale 0: their probability is exactly 0, and whatever
                 // the storage holds there (it need not be initialised) must not turn that into a NaN.
-                const float vz = pre_valid ? pre_c : 0.0f;
-                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? pre_b : 0.0f;
+                // The probability of this key meets value codes unpacked with weight 4^-g: it carries 4^g
+                // (through the value scale), and tau's multiplier is BASE + 4^-g z.
+                const int g2 = 2 * value_register_class<BITS>(slot & 15);
+                const float vz = pre_valid ? Unpack<BITS>::kValueBase + ldexpf(pre_c - Unpack<BITS>::kStoredOffset, -g2) : 0.0f;
+                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? ldexpf(pre_b, g2) : 0.0f;
                 const uint16_t v_h = bf16_bits(vz);
                 const uint16_t v_l = bf16_bits(vz - bf16_val(v_h));
                 reinterpret_cast<uint16_t *>(buf + St::kVzHi)[slot] = v_h;

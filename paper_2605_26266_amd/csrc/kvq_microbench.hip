@@ -33,6 +33,7 @@ enum Op { kFma, kMul, kAndOr, kShift, kCvtPk, kDot2, kExp2, kMax3 };
 
 // W waves per SIMD; each wave runs kIters x 8 steps of (one 32x32x16 MFMA on one of CH accumulators,
 // then NV independent vector instructions of kind OP).
+// CH = -1: the MFMA takes the constant 0 as its C operand (nothing accumulated, no accumulator read).
 template <int W, int CH, int NV, Op OP>
 __global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t mask, uint32_t base)
 {
@@ -56,6 +57,11 @@ __global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t ma
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             if (CH > 0) c[j % (CH > 0 ? CH : 1)] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c[j % (CH > 0 ? CH : 1)], 0, 0, 0);
+            if (CH < 0) {
+                f32x16 zero;
+                for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+                c[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, zero, 0, 0, 0);
+            }
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int k = (j * NV + v) & 15, k1 = (k + 1) & 15;
@@ -169,6 +175,8 @@ int main()
     printf("| 12 | %.2f | %.2f |\n", step_ns<1, 4, 12, kFma>(out), step_ns<2, 4, 12, kFma>(out));
     printf("| 16 | %.2f | %.2f |\n", step_ns<1, 4, 16, kFma>(out), step_ns<2, 4, 16, kFma>(out));
     printf("| 16, no MFMA | %.2f | %.2f |\n", step_ns<1, 0, 16, kFma>(out), step_ns<2, 0, 16, kFma>(out));
+    printf("| 12, MFMA with C = 0 | %.2f | %.2f |\n", step_ns<1, -1, 12, kFma>(out), step_ns<2, -1, 12, kFma>(out));
+    printf("| 16, MFMA with C = 0 | %.2f | %.2f |\n", step_ns<1, -1, 16, kFma>(out), step_ns<2, -1, 16, kFma>(out));
 
     printf("\n## Marginal cost of one vector instruction next to MFMAs (step = 1 MFMA + N instr; ns per SIMD)\n\n");
     printf("| instruction | 1w N=8 | 1w N=16 | 1w ns/instr | 2w N=8 | 2w N=16 | 2w ns/instr |\n|---|---|---|---|---|---|---|\n");

@@ -42,6 +42,11 @@ def _load():
     lib.kvqo_num_threads.restype = ci
     lib.kvqo_hadamard.argtypes = [ci, dp, dp]
     lib.kvqo_quantize_rows.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp]
+    lib.kvqo_quantize_rows_fp8meta.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp, bp]
+    lib.kvqo_e4m3_ceil.argtypes = [cd, bp]
+    lib.kvqo_e4m3_ceil.restype = cd
+    lib.kvqo_bf16_round.argtypes = [cd]
+    lib.kvqo_bf16_round.restype = cd
     lib.kvqo_dequantize_rows.argtypes = [i64, ci, ci, bp, fp, fp, dp]
     lib.kvqo_log_sinhc.argtypes = [cd]
     lib.kvqo_log_sinhc.restype = cd
@@ -73,21 +78,39 @@ def hadamard(x) -> np.ndarray:
     return u
 
 
-def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True
+def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True, fp8_meta: bool = False
              ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """x [rows][d] -> codes uint8 [rows][d], scale float32 [rows][G], zero float32 [rows][G]."""
+    """x [rows][d] -> codes uint8 [rows][d], scale float32 [rows][G], zero float32 [rows][G].
+
+    fp8_meta: the stored scale is an FP8 E4M3 value and the stored zero-point a BF16 value."""
     x = _d(x)
     rows, d = x.shape
     group = d if group is None else group
     codes = np.empty((rows, d), dtype=np.uint8)
     scale = np.empty((rows, d // group), dtype=np.float32)
     zero = np.empty((rows, d // group), dtype=np.float32)
-    rc = _load().kvqo_quantize_rows(rows, d, bits, group, int(rotate), _p(x, ctypes.c_double),
-                                    _p(codes, ctypes.c_uint8), _p(scale, ctypes.c_float),
-                                    _p(zero, ctypes.c_float))
+    if fp8_meta:
+        rc = _load().kvqo_quantize_rows_fp8meta(rows, d, bits, group, int(rotate), _p(x, ctypes.c_double),
+                                                _p(codes, ctypes.c_uint8), _p(scale, ctypes.c_float),
+                                                _p(zero, ctypes.c_float), None)
+    else:
+        rc = _load().kvqo_quantize_rows(rows, d, bits, group, int(rotate), _p(x, ctypes.c_double),
+                                        _p(codes, ctypes.c_uint8), _p(scale, ctypes.c_float),
+                                        _p(zero, ctypes.c_float))
     if rc:
         raise ValueError("quantize: bad arguments")
     return codes, scale, zero
+
+
+def e4m3_ceil(x: float) -> Tuple[float, int]:
+    """Smallest FP8 E4M3 value >= x (x > 0) and its encoding."""
+    b = ctypes.c_uint8(0)
+    v = float(_load().kvqo_e4m3_ceil(float(x), ctypes.byref(b)))
+    return v, int(b.value)
+
+
+def bf16_round(x: float) -> float:
+    return float(_load().kvqo_bf16_round(float(x)))
 
 
 def dequantize(codes, scale, zero) -> np.ndarray:
@@ -141,7 +164,8 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
 
 
 def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
-                    sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True):
+                    sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True,
+                    fp8_meta: bool = False):
     """Whole path for [token][head][d] inputs: quantize the cached K/V per head, then attention.
 
     Returns (out [m][heads][d], P_S [heads][m], quantized) where quantized holds the
@@ -153,8 +177,8 @@ def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: 
     mass = np.empty((heads, m), dtype=np.float64)
     quantized = []
     for h in range(heads):
-        kc, ks, kz = quantize(np.asarray(k_cached)[:, h, :], bits, group, rotate)
-        vc, vs, vz = quantize(np.asarray(v_cached)[:, h, :], bits, group, rotate)
+        kc, ks, kz = quantize(np.asarray(k_cached)[:, h, :], bits, group, rotate, fp8_meta)
+        vc, vs, vz = quantize(np.asarray(v_cached)[:, h, :], bits, group, rotate, fp8_meta)
         o, p = attention(q[:, h, :], dequantize(kc, ks, kz), ks, dequantize(vc, vs, vz),
                          np.asarray(k_cur)[:, h, :], np.asarray(v_cur)[:, h, :], sigma, correction, rotate)
         out[:, h, :] = o

@@ -143,6 +143,126 @@ int kvqo_quantize_rows(int64_t rows, int d, int bits, int group, int rotate,
     return failed;
 }
 
+/*
+ * FP8 E4M3 (the 8-bit format with 4 exponent bits, bias 7, 3 mantissa bits, no
+ * infinities, largest finite value 448, subnormals m * 2^-9): the smallest
+ * representable value that is >= x, for x > 0.  Values above 448 saturate at
+ * 448 (the range is then not covered; callers see the clamp in the codes).
+ * Returns the value; *byte receives its encoding.
+ */
+double kvqo_e4m3_ceil(double x, uint8_t *byte)
+{
+    if (!(x > 0.0)) { if (byte) *byte = 0; return 0.0; }
+    if (x > 448.0) x = 448.0;
+    int e;                      /* x = f * 2^e, f in [0.5, 1)  =>  x in [2^(e-1), 2^e) */
+    (void)frexp(x, &e);
+    int E = e - 1;              /* floor(log2 x) */
+    if (E < -6) E = -6;         /* subnormals share the spacing of the lowest binade */
+    const double ulp = ldexp(1.0, E - 3);
+    const double v = ceil(x / ulp) * ulp;   /* x / ulp is exact (power of two) */
+    if (byte) {
+        int ev;
+        (void)frexp(v, &ev);
+        int Ev = ev - 1;
+        unsigned bits;
+        if (Ev < -6) {
+            bits = (unsigned)(v / ldexp(1.0, -9));                 /* subnormal: exponent field 0 */
+        } else {
+            const unsigned m = (unsigned)(v / ldexp(1.0, Ev - 3)) - 8u;
+            bits = ((unsigned)(Ev + 7) << 3) | m;
+        }
+        *byte = (uint8_t)bits;
+    }
+    return v;
+}
+
+/* Nearest BF16 value (8 significant bits, ties to even) of a double that is an
+ * integer or any value well inside the float range. */
+double kvqo_bf16_round(double x)
+{
+    if (x == 0.0 || x != x) return x;
+    int e;
+    (void)frexp(x, &e);                 /* |x| in [2^(e-1), 2^e) */
+    const double ulp = ldexp(1.0, e - 8);
+    return rint(x / ulp) * ulp;         /* rint: ties to even */
+}
+
+/*
+ * Group-wise asymmetric round-to-nearest quantization with the metadata format
+ * of "Effective bitwidth" / the storage note of the cost appendix: per group one
+ * FP8 E4M3 scale and one BF16 zero-point (24 bits per group).  The paper fixes
+ * the formats, not the rounding; the reading taken here keeps Eq. 1's promise
+ * that scale and zero-point cover [min, max]:
+ *
+ *   u      = H_d x  (rotate)            lo, hi over the group as in kvqo_quantize_rows
+ *   step   = (hi - lo) / L * n          n = 1/sqrt(d) with rotation, 1 without
+ *   s8     = smallest E4M3 value >= step            (the stored scale)
+ *   inv    = n / s8
+ *   z      = -rint(lo * inv),  zb = BF16(z)         (the stored zero-point)
+ *   code   = clamp(rint(u * inv) + zb, 0, L)
+ * Every operation is one IEEE double operation in this order.
+ * scale, zero: [rows][d/group] floats holding exactly the stored values;
+ * scale_bytes (nullable): the E4M3 encodings.
+ */
+int kvqo_quantize_rows_fp8meta(int64_t rows, int d, int bits, int group, int rotate,
+                               const double *x, uint8_t *codes, float *scale, float *zero,
+                               uint8_t *scale_bytes)
+{
+    if (rows < 0 || d <= 0 || group <= 0 || d % group != 0) return 1;
+    if (bits < 1 || bits > 8) return 1;
+    if (rotate && !is_pow2(d)) return 1;
+    const double L = (double)((1 << bits) - 1);
+    const double norm = rotate ? inv_sqrt_d(d) : 1.0;
+    const int G = d / group;
+    int failed = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < rows; ++t) {
+        double *u = (double *)malloc(sizeof(double) * (size_t)d);
+        if (!u) { failed = 1; continue; }
+        const double *xr = x + t * d;
+        if (rotate) kvqo_hadamard(d, xr, u);
+        else memcpy(u, xr, sizeof(double) * (size_t)d);
+        for (int j = 0; j < G; ++j) {
+            const double *ug = u + j * group;
+            uint8_t *cg = codes + t * d + j * group;
+            double lo = ug[0], hi = ug[0];
+            for (int c = 1; c < group; ++c) {
+                if (ug[c] < lo) lo = ug[c];
+                if (ug[c] > hi) hi = ug[c];
+            }
+            if (hi == lo) {
+                if (lo > 0.0) lo = 0.0;
+                if (hi < 0.0) hi = 0.0;
+            }
+            if (hi == lo) {
+                for (int c = 0; c < group; ++c) cg[c] = 0;
+                scale[t * G + j] = 0.0f;
+                zero[t * G + j] = 0.0f;
+                if (scale_bytes) scale_bytes[t * G + j] = 0;
+                continue;
+            }
+            const double range = hi - lo;
+            const double step = range / L * norm;
+            uint8_t sb;
+            const double s8 = kvqo_e4m3_ceil(step, &sb);
+            const double inv = norm / s8;
+            const double z = -rint(lo * inv);
+            const double zb = kvqo_bf16_round(z);
+            for (int c = 0; c < group; ++c) {
+                double k = rint(ug[c] * inv) + zb;
+                if (k < 0.0) k = 0.0;
+                if (k > L) k = L;
+                cg[c] = (uint8_t)k;
+            }
+            scale[t * G + j] = (float)s8;
+            zero[t * G + j] = (float)zb;
+            if (scale_bytes) scale_bytes[t * G + j] = sb;
+        }
+        free(u);
+    }
+    return failed;
+}
+
 /* Reconstruction x^ = (x_q - z) * step (sentence after Eq. 1), in the basis the
  * codes were taken in.  out: [rows][d] doubles. */
 int kvqo_dequantize_rows(int64_t rows, int d, int group, const uint8_t *codes,

@@ -5,9 +5,10 @@
  * Correction for KV-Cache Compression in Video Diffusion":
  *
  *   kvq_quantize_append   rotate (Hadamard), quantize (asymmetric round-to-nearest,
- *                         per token) and bit-pack one chunk's keys and values into
- *                         the cache                      [Preliminaries: Eq. 1,
- *                         "Quantization granularity", "Hadamard rotation"]
+ *                         per token or per group of channels of a token) and bit-pack
+ *                         one chunk's keys and values into the cache
+ *                         [Preliminaries: Eq. 1, "Quantization granularity",
+ *                         "Hadamard rotation"; "Effective bitwidth" for the metadata]
  *   kvq_chunk_attention   current-chunk queries attend to the packed cache of earlier
  *                         chunks and to the unquantized keys/values of the current
  *                         chunk in one joint softmax, with the second-order Taylor
@@ -46,28 +47,38 @@ typedef struct kvq_cache kvq_cache; /* opaque host object */
 typedef enum {
     KVQ_OK = 0,
     KVQ_ERR_INVALID_ARG = 1, /* null pointer, negative size, misaligned buffer, bad range */
-    KVQ_ERR_UNSUPPORTED = 2, /* head_dim not 64/128, bits not 2/4, group_size != head_dim, rotate != 1 */
+    KVQ_ERR_UNSUPPORTED = 2, /* head_dim not 64/128, bits not 2/4, group_size not 32/64/head_dim, rotate != 1,
+                                groups smaller than a token without KVQ_META_FP8_BF16 */
     KVQ_ERR_CAPACITY = 3,    /* append would exceed capacity_tokens */
     KVQ_ERR_HIP = 4          /* the HIP runtime refused a launch */
 } kvq_status;
 
 typedef enum { KVQ_BF16 = 0, KVQ_FP32 = 1 } kvq_dtype;
 
+/* Storage format of the (scale, zero-point) pairs. */
+typedef enum {
+    KVQ_META_FP32 = 0,    /* one fp32 scale and one fp32 zero-point per token (group_size == head_dim only) */
+    KVQ_META_FP8_BF16 = 1 /* one FP8 E4M3 scale and one BF16 zero-point per group: 24 bits per group, the
+                             format of the paper's effective-bitwidth formula B + 24/g */
+} kvq_meta_format;
+
 typedef struct {
     int32_t num_heads;       /* >= 1 */
     int32_t head_dim;        /* 64 or 128 */
     int32_t bits;            /* 2 or 4 */
-    int32_t group_size;      /* channels sharing one (scale, zero-point); must equal head_dim (per token) */
+    int32_t group_size;      /* channels of a token sharing one (scale, zero-point): 32, 64 or head_dim */
     int32_t rotate;          /* must be 1: normalised Sylvester-Hadamard rotation before quantization */
-    int32_t io_dtype;        /* kvq_dtype of q/k/v/out.  KVQ_BF16 with head_dim 128 runs on the matrix
-                                cores; KVQ_FP32 (and head_dim 64) runs an fp32 vector kernel */
+    int32_t io_dtype;        /* kvq_dtype of q/k/v/out.  KVQ_BF16 with head_dim 128 and KVQ_META_FP32 runs on the
+                                matrix cores; everything else runs an fp32 vector kernel */
+    int32_t meta_format;     /* kvq_meta_format */
     int64_t capacity_tokens; /* >= 1; storage is sized for this many tokens per head */
 } kvq_cache_desc;
 
-/* Device bytes the caller must provide for a cache of this description:
- * 2 * num_heads * cap32 * (head_dim*bits/8 + 8) with cap32 = capacity rounded up to 32 tokens
- * (codes plus one float scale and one float zero-point per token, for K and for V).
- * Returns 0 for an invalid or unsupported description. */
+/* Device bytes the caller must provide for a cache of this description, with cap32 = capacity rounded
+ * up to 32 tokens:
+ *   KVQ_META_FP32      2 * num_heads * cap32 * (head_dim*bits/8 + 8)
+ *   KVQ_META_FP8_BF16  2 * num_heads * cap32 * (head_dim*bits/8 + 3 * head_dim/group_size)
+ * (codes plus the metadata, for K and for V).  Returns 0 for an invalid or unsupported description. */
 size_t kvq_cache_bytes(const kvq_cache_desc *desc);
 
 /* Creates the host object over caller-provided device storage (`dev_mem`, at least
@@ -90,8 +101,11 @@ kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len);
  * normalised Hadamard matrix, quantized to `bits` with one (scale, zero-point) per token
  *     step = (max - min) / (2^bits - 1),  z = -round(min/step),
  *     code = clamp(round(x/step) + z, 0, 2^bits - 1)            (round: nearest, ties to even)
- * and packed.  A constant vector has its range widened to include 0; an all-zero vector gets
- * step 0.  The rotation is carried out exactly in double precision, so for inputs whose
+ * and packed.  With KVQ_META_FP8_BF16 the same is done per group of group_size rotated channels, with
+ * the stored step the smallest FP8 E4M3 value >= (max - min)/(2^bits - 1) (so that the grid still covers
+ * [min, max]; steps above 448 saturate) and the stored zero-point the BF16 value nearest to z; codes are
+ * taken with the stored values.  A constant vector (group) has its range widened to include 0; an
+ * all-zero one gets step 0.  The rotation is carried out exactly in double precision, so for inputs whose
  * nonzero magnitudes in one vector span at most 2^38 (BF16 values) the codes, scales and
  * zero-points are a bit-exact function of the input.
  *
@@ -105,7 +119,8 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
  * Corrected chunk attention.  For every head and query row m:
  *     cached key i in [cache_start, cache_start + cache_len):
  *         s_i = softmax_scale * (Hn q_m) . k^_i  -  b_mi,
- *         b_mi = correction ? softmax_scale^2 * step_i^2 * ||q_m||^2 / 24 : 0
+ *         b_mi = correction ? softmax_scale^2 / 24 * sum_j step_ij^2 * ||(Hn q_m)_j||^2 : 0
+ *         (j runs over the groups; per token this is softmax_scale^2 * step_i^2 * ||q_m||^2 / 24)
  *     current key j in [0, n_cur):   s_j = softmax_scale * q_m . k_cur_j
  *     p = softmax over all of them;  out_m = sum_i p_i v^_i (rotated back) + sum_j p_j v_cur_j
  *     mass_cached[head][m] = sum over cached keys of p      (attention mass P_S; P_R = 1 - P_S)
@@ -135,8 +150,8 @@ kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start,
 /*
  * Canonical view of cached tokens [start, start + count), for parity checks and dump/restore.
  * which: 0 = keys, 1 = values.  codes: device uint8 [num_heads][count][head_dim], one code per
- * byte, channel order of the rotated vector.  scales, zeros: device float [num_heads][count].
- * Any of the three output pointers may be NULL.
+ * byte, channel order of the rotated vector.  scales, zeros: device float [num_heads][count][G],
+ * G = head_dim / group_size, holding exactly the stored values.  Any of the three output pointers may be NULL.
  */
 kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count,
                             uint8_t *codes, float *scales, float *zeros, void *hip_stream);

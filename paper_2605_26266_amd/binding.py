@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libkvq.so")
 
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_CAPACITY, KVQ_ERR_HIP = range(5)
 KVQ_BF16, KVQ_FP32 = 0, 1
+KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
 
 # Every symbol declared in include/kvq.h.
 EXPORTED = (
@@ -28,7 +29,7 @@ EXPORTED = (
 class kvq_cache_desc(ctypes.Structure):
     _fields_ = [("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("bits", ctypes.c_int32),
                 ("group_size", ctypes.c_int32), ("rotate", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
-                ("capacity_tokens", ctypes.c_int64)]
+                ("meta_format", ctypes.c_int32), ("capacity_tokens", ctypes.c_int64)]
 
 
 class KvqError(RuntimeError):
@@ -94,9 +95,9 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 
 def make_desc(num_heads: int, head_dim: int, bits: int, capacity_tokens: int, io_dtype: int = KVQ_BF16,
-              group_size: Optional[int] = None, rotate: int = 1) -> kvq_cache_desc:
+              group_size: Optional[int] = None, rotate: int = 1, meta_format: int = KVQ_META_FP32) -> kvq_cache_desc:
     return kvq_cache_desc(num_heads, head_dim, bits, head_dim if group_size is None else group_size, rotate,
-                          io_dtype, capacity_tokens)
+                          io_dtype, meta_format, capacity_tokens)
 
 
 def kvq_cache_bytes(desc: kvq_cache_desc) -> int:
@@ -208,12 +209,14 @@ def kvq_cache_export(cache: Cache, which: int, start: int, count: int, codes: Op
 
 
 def export_all(cache: Cache, which: int, start: int = 0, count: Optional[int] = None):
-    """Allocate outputs and export: (codes uint8 [H][count][d], scales [H][count], zeros [H][count])."""
+    """Allocate outputs and export: (codes uint8 [H][count][d], scales, zeros); scales and zeros are
+    [H][count] for per-token caches and [H][count][G] for KVQ_META_FP8_BF16 caches."""
     count = len(cache) - start if count is None else count
     H, d = cache.desc.num_heads, cache.desc.head_dim
     dev = cache.storage.device
     codes = torch.empty((H, count, d), dtype=torch.uint8, device=dev)
-    scales = torch.empty((H, count), dtype=torch.float32, device=dev)
-    zeros = torch.empty((H, count), dtype=torch.float32, device=dev)
+    meta_shape = (H, count) if cache.desc.meta_format == KVQ_META_FP32 else (H, count, d // cache.desc.group_size)
+    scales = torch.empty(meta_shape, dtype=torch.float32, device=dev)
+    zeros = torch.empty(meta_shape, dtype=torch.float32, device=dev)
     kvq_cache_export(cache, which, start, count, codes, scales, zeros)
     return codes, scales, zeros

@@ -20,7 +20,10 @@ kvq_status check_desc(const kvq_cache_desc *d)
     if (d->io_dtype != KVQ_BF16 && d->io_dtype != KVQ_FP32) return KVQ_ERR_INVALID_ARG;
     if (d->head_dim != 64 && d->head_dim != 128) return KVQ_ERR_UNSUPPORTED;
     if (d->bits != 2 && d->bits != 4) return KVQ_ERR_UNSUPPORTED;
-    if (d->group_size != d->head_dim) return KVQ_ERR_UNSUPPORTED;
+    if (d->meta_format != KVQ_META_FP32 && d->meta_format != KVQ_META_FP8_BF16) return KVQ_ERR_INVALID_ARG;
+    if (d->group_size != d->head_dim && d->group_size != 32 && d->group_size != 64) return KVQ_ERR_UNSUPPORTED;
+    if (d->group_size > d->head_dim) return KVQ_ERR_UNSUPPORTED;
+    if (d->group_size != d->head_dim && d->meta_format != KVQ_META_FP8_BF16) return KVQ_ERR_UNSUPPORTED;
     if (d->rotate != 1) return KVQ_ERR_UNSUPPORTED;
     if (d->capacity_tokens > ((int64_t)1 << 40)) return KVQ_ERR_INVALID_ARG;
     return KVQ_OK;
@@ -49,7 +52,8 @@ size_t kvq_cache_bytes(const kvq_cache_desc *desc)
 {
     if (check_desc(desc) != KVQ_OK) return 0;
     const int64_t cap32 = round_up_tile(desc->capacity_tokens);
-    const int64_t per_token = desc->head_dim * desc->bits / 8 + 8;
+    const int64_t meta = desc->meta_format == KVQ_META_FP32 ? 8 : 3 * (desc->head_dim / desc->group_size);
+    const int64_t per_token = desc->head_dim * desc->bits / 8 + meta;
     return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token);
 }
 
@@ -73,10 +77,23 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
     kvq::CacheView &v = c->view;
     v.k_codes = reinterpret_cast<uint32_t *>(p); p += code_bytes;
     v.v_codes = reinterpret_cast<uint32_t *>(p); p += code_bytes;
-    v.k_scale = reinterpret_cast<float *>(p); p += meta_bytes;
-    v.k_negzero = reinterpret_cast<float *>(p); p += meta_bytes;
-    v.v_scale = reinterpret_cast<float *>(p); p += meta_bytes;
-    v.v_zero_off = reinterpret_cast<float *>(p);
+    v.k_scale = v.k_negzero = v.v_scale = v.v_zero_off = nullptr;
+    v.k_scale8 = v.v_scale8 = nullptr;
+    v.k_zero16 = v.v_zero16 = nullptr;
+    v.group_size = desc->group_size;
+    v.meta_format = desc->meta_format;
+    if (desc->meta_format == KVQ_META_FP32) {
+        v.k_scale = reinterpret_cast<float *>(p); p += meta_bytes;
+        v.k_negzero = reinterpret_cast<float *>(p); p += meta_bytes;
+        v.v_scale = reinterpret_cast<float *>(p); p += meta_bytes;
+        v.v_zero_off = reinterpret_cast<float *>(p);
+    } else {
+        const int64_t groups = H * c->cap32 * (desc->head_dim / desc->group_size);   // multiple of 32
+        v.k_zero16 = reinterpret_cast<uint16_t *>(p); p += 2 * groups;
+        v.v_zero16 = reinterpret_cast<uint16_t *>(p); p += 2 * groups;
+        v.k_scale8 = reinterpret_cast<uint8_t *>(p); p += groups;
+        v.v_scale8 = reinterpret_cast<uint8_t *>(p);
+    }
     v.cap_tiles = c->cap32 / kvq::kTileTokens;
     v.num_heads = desc->num_heads;
     v.head_dim = desc->head_dim;
@@ -159,7 +176,8 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.correction = correction;
     a.out = out;
     a.mass_cached = mass_cached;
-    const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128;
+    const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
+                             d.meta_format == KVQ_META_FP32;
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = matrix_path ? kvq::launch_attention_mfma(a, s) : kvq::launch_attention_simt(a, s);
     return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
@@ -208,6 +226,6 @@ const char *kvq_status_string(kvq_status status)
     return "unknown status";
 }
 
-const char *kvq_version(void) { return "0.1"; }
+const char *kvq_version(void) { return "0.2"; }
 
 }  // extern "C"

@@ -3,10 +3,11 @@
 // Used for KVQ_FP32 caches, for head_dim 64, and by kvq_chunk_attention_fp32.  It follows
 // Alg. 1 of the paper literally in single precision, one workgroup of d threads per
 // (head, query row):
-//   * rotate the query (butterflies in LDS), nu = ||q||^2;
+//   * rotate the query (butterflies in LDS), nu_j = ||(Hn q)_j||^2 per group of channels that shares a
+//     (scale, zero-point) (one group = the whole vector for per-token quantization);
 //   * pass 1: every thread scores a strided subset of the keys (cached keys from their packed
-//     codes, corrected by b = scale^2 * step^2 * nu / 24; current keys from k_cur) to find the
-//     row maximum;
+//     codes, corrected by b = scale^2 / 24 * sum_j step_j^2 nu_j; current keys from k_cur) to find
+//     the row maximum;
 //   * pass 2: scores again, p = exp(s - max); blocks of d weights go through LDS so that thread c
 //     accumulates output channel c; the cached part is accumulated in the rotated basis and
 //     rotated back before the current part is added.
@@ -52,6 +53,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     __shared__ float q_raw[D];
     __shared__ float p_blk[D];
     __shared__ float scratch[D];
+    __shared__ float corr_g[4];  // softmax_scale^2 / 24 * nu_j per group (at most 4 groups)
     const CacheView &cv = a.cv;
     const int c = threadIdx.x;
     const int head = blockIdx.y;
@@ -66,8 +68,22 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     q_rot[c] = qc;
     fwht_lds<D>(q_rot, c);
     q_rot[c] *= norm;
-    const float nu = block_reduce<D>(qc * qc, scratch, c, false);
-    const float corr_coef = a.correction ? sigma * sigma * nu * (1.0f / 24.0f) : 0.0f;
+    const bool fp8_meta = cv.meta_format == KVQ_META_FP8_BF16;
+    const int group = fp8_meta ? cv.group_size : D;
+    const int G = D / group;
+    {
+        // per-group squared norms of the rotated query (Appendix "Extension to QuaRot"); with one group
+        // this is ||q||^2
+        __syncthreads();
+        scratch[c] = q_rot[c] * q_rot[c];
+        __syncthreads();
+        if (c < G) {
+            float nu = 0.0f;
+            for (int i = 0; i < group; ++i) nu += scratch[c * group + i];
+            corr_g[c] = a.correction ? sigma * sigma * nu * (1.0f / 24.0f) : 0.0f;
+        }
+        __syncthreads();
+    }
 
     const int64_t meta0 = (int64_t)head * cv.cap_tiles * kTileTokens;
     const uint32_t *k_head = cv.k_codes + (int64_t)head * cv.cap_tiles * tile_words(D, BITS);
@@ -76,8 +92,17 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     auto cached_score = [&](int64_t t) -> float {
         const uint32_t *tile = k_head + (t / kTileTokens) * tile_words(D, BITS);
         const int tt = (int)(t % kTileTokens);
-        const float scale = cv.k_scale[meta0 + t];
-        const float zero = -cv.k_negzero[meta0 + t] - off;
+        float scale_g[4], zero_g[4], b = 0.0f;
+        for (int g = 0; g < G; ++g) {
+            if (fp8_meta) {
+                scale_g[g] = e4m3_to_float(cv.k_scale8[(meta0 + t) * G + g]);
+                zero_g[g] = bf16_to_float(cv.k_zero16[(meta0 + t) * G + g]);
+            } else {
+                scale_g[g] = cv.k_scale[meta0 + t];
+                zero_g[g] = -cv.k_negzero[meta0 + t] - off;
+            }
+            b += corr_g[g] * scale_g[g] * scale_g[g];
+        }
         float dot = 0.0f;
         for (int hh = 0; hh < 2; ++hh) {
             const uint32_t *slot = tile + (hh * 32 + tt) * WPL;
@@ -88,12 +113,13 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
                     const int ch = 16 * slab + 8 * hh + 2 * (j & 3);
                     const float c0 = (float)((word >> (BITS * j)) & MASK);
                     const float c1 = (float)((word >> (BITS * j + 16)) & MASK);
+                    const float scale = scale_g[ch / group], zero = zero_g[ch / group];   // ch, ch + 1: same group
                     dot = fmaf(q_rot[ch], (c0 - zero) * scale, dot);
                     dot = fmaf(q_rot[ch + 1], (c1 - zero) * scale, dot);
                 }
             }
         }
-        return sigma * dot - corr_coef * scale * scale;
+        return sigma * dot - b;
     };
     auto current_score = [&](int64_t j) -> float {
         const T *kp = static_cast<const T *>(a.k_cur) + j * a.stride_token + (int64_t)head * a.stride_head;
@@ -124,8 +150,16 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
             value_code_pos(D, BITS, (int)(t % kTileTokens), c, word, shift);
             const uint32_t w = v_head[(t / kTileTokens) * tile_words(D, BITS) + word];
             const float code = (float)((w >> shift) & MASK);
-            const float vz = cv.v_zero_off[meta0 + t] - off;
-            acc = fmaf(p_blk[jj], (code - vz) * cv.v_scale[meta0 + t], acc);
+            float vz, vs;
+            if (fp8_meta) {
+                const int64_t gi = (meta0 + t) * G + c / group;
+                vs = e4m3_to_float(cv.v_scale8[gi]);
+                vz = bf16_to_float(cv.v_zero16[gi]);
+            } else {
+                vs = cv.v_scale[meta0 + t];
+                vz = cv.v_zero_off[meta0 + t] - off;
+            }
+            acc = fmaf(p_blk[jj], (code - vz) * vs, acc);
         }
     }
     // Rotate the cached part back: out_S = Hn^T acc (Hn symmetric).

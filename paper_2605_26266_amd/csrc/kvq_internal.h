@@ -41,7 +41,20 @@ struct CacheView {
     float *v_zero_off;   // [H][cap32]   zero + OFFSET
     int64_t cap_tiles;   // tiles per head
     int32_t num_heads, head_dim, bits, io_dtype;
+    // KVQ_META_FP8_BF16 caches use these instead of the four float arrays (G = head_dim / group_size):
+    int32_t group_size, meta_format;
+    uint8_t *k_scale8, *v_scale8;    // [H][cap32][G]  FP8 E4M3 encodings
+    uint16_t *k_zero16, *v_zero16;   // [H][cap32][G]  BF16 encodings
 };
+
+// FP8 E4M3 (bias 7, 3 mantissa bits, subnormals m * 2^-9, no infinities) -> float.  Scales are never
+// negative and never the NaN encoding.
+__host__ __device__ inline float e4m3_to_float(uint8_t b)
+{
+    const int e = (b >> 3) & 15, m = b & 7;
+    const float mag = e == 0 ? (float)m * 0.001953125f : (float)(8 + m) * (float)(1u << e) * 0.0009765625f;
+    return (b & 0x80) ? -mag : mag;   // (8 + m) * 2^(e - 10) = (1 + m/8) * 2^(e - 7)
+}
 
 __host__ __device__ inline int words_per_lane(int d, int bits) { return d * bits / 64; }
 __host__ __device__ inline int tile_words(int d, int bits) { return d * bits; }  // 64 * WPL

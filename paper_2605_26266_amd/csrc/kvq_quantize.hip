@@ -92,7 +92,30 @@ template <> struct Vec<float> {
     }
 };
 
-template <int D, int BITS, typename T>
+// Smallest FP8 E4M3 value >= x for x > 0 (448 beyond the format's range) and its encoding.  Scaling by a
+// power of two, ceil and scaling back are all exact in double.
+__device__ inline double e4m3_ceil(double x, uint32_t &byte)
+{
+    x = x > 448.0 ? 448.0 : x;
+    int e = (int)((__double_as_longlong(x) >> 52) & 0x7ff) - 1023;   // floor(log2 x) for normal doubles
+    e = e < -6 ? -6 : e;                                              // subnormals share the lowest binade's spacing
+    const double up = __longlong_as_double((long long)(1023 + 3 - e) << 52);     // 2^(3 - e)
+    const double down = __longlong_as_double((long long)(1023 - 3 + e) << 52);   // 2^(e - 3)
+    const double n = __builtin_ceil(x * up);   // in [1, 16]; 16 means the next binade
+    const double v = n * down;
+    const int ev = (int)((__double_as_longlong(v) >> 52) & 0x7ff) - 1023;
+    if (ev < -6) {
+        byte = (uint32_t)n;                    // subnormal: m * 2^-9 with e == -6, so n = m
+    } else {
+        const double m8 = v * __longlong_as_double((long long)(1023 + 3 - ev) << 52);   // 8 + m
+        byte = ((uint32_t)(ev + 7) << 3) | ((uint32_t)m8 - 8u);
+    }
+    return v;
+}
+
+// GROUP == 0: one fp32 (scale, zero-point) per token.  GROUP > 0: one FP8 E4M3 scale and one BF16
+// zero-point per GROUP rotated channels; codes are taken with the stored values.
+template <int D, int BITS, int GROUP, typename T>
 __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, const T *__restrict__ k,
                                                              const T *__restrict__ v, int64_t old_len,
                                                              int64_t n_tokens, int64_t stride_token,
@@ -156,21 +179,39 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
             lo = x[i] < lo ? x[i] : lo;
             hi = x[i] > hi ? x[i] : hi;
         }
+        constexpr int kGroupCh = GROUP == 0 ? D : GROUP;
+        constexpr int kLanesPerGroup = kGroupCh / EPL;   // lanes that share one (scale, zero-point)
 #pragma unroll
-        for (int msk = 1; msk < 8; msk <<= 1) {
+        for (int msk = 1; msk < kLanesPerGroup; msk <<= 1) {
             const double olo = __shfl_xor(lo, msk), ohi = __shfl_xor(hi, msk);
             lo = olo < lo ? olo : lo;
             hi = ohi > hi ? ohi : hi;
         }
-        if (hi == lo) {  // constant vector: widen the range to include 0
+        if (hi == lo) {  // constant vector (group): widen the range to include 0
             lo = lo > 0.0 ? 0.0 : lo;
             hi = hi < 0.0 ? 0.0 : hi;
         }
-        const bool degenerate = hi == lo;  // all-zero vector
+        const bool degenerate = hi == lo;  // all-zero vector (group)
         const double range = hi - lo;
-        const double inv = degenerate ? 0.0 : (double)L / range;
-        const double step = degenerate ? 0.0 : range / (double)L;
-        const double z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+        double inv, z;
+        float scale, zero;
+        uint32_t scale_byte = 0u;
+        if constexpr (GROUP == 0) {
+            inv = degenerate ? 0.0 : (double)L / range;
+            const double step = degenerate ? 0.0 : range / (double)L;
+            z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+            scale = (float)(step * norm);
+            zero = (float)z;
+        } else {
+            // step in the normalised domain, rounded up to the format; everything after uses the stored values
+            const double step = range / (double)L * norm;
+            const double s8 = degenerate ? 0.0 : e4m3_ceil(step, scale_byte);
+            inv = degenerate ? 0.0 : norm / s8;
+            const double zi = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+            zero = bf16_to_float(float_to_bf16((float)zi));
+            z = (double)zero;
+            scale = (float)s8;
+        }
         int code[EPL];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
@@ -179,8 +220,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
             c = c > (double)L ? (double)L : c;
             code[i] = (int)c;
         }
-        const float scale = (float)(step * norm);
-        const float zero = (float)z;
+        // KVQ_META_FP8_BF16: the first lane of each group stores the group's pair
+        const bool group_writer = GROUP != 0 && (l8 % kLanesPerGroup) == 0;
+        const int64_t group_idx = GROUP != 0 ? meta_idx * (D / kGroupCh) + l8 / kLanesPerGroup : 0;
 
         const bool tail = t >= hi_t;  // slot of this tile that no append has reached yet: keep it finite
         if (pass == 0) {
@@ -215,15 +257,25 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
                     const int hh = l8 & 1;
                     if (BITS == 4 || (l8 & 2) == 0) k_tile[(hh * 32 + row) * WPL + q] = mine[0];
                 }
-                if (l8 == 2) cv.k_scale[meta_idx] = scale;
-                if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                if constexpr (GROUP == 0) {
+                    if (l8 == 2) cv.k_scale[meta_idx] = scale;
+                    if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                } else if (group_writer) {
+                    cv.k_scale8[group_idx] = (uint8_t)scale_byte;
+                    cv.k_zero16[group_idx] = float_to_bf16(zero);
+                }
             }
         } else {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) v_stage[row][l8 * EPL + i] = (uint8_t)code[i];
             if (valid || tail) {
-                if (l8 == 2) cv.v_scale[meta_idx] = scale;
-                if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                if constexpr (GROUP == 0) {
+                    if (l8 == 2) cv.v_scale[meta_idx] = scale;
+                    if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                } else if (group_writer) {
+                    cv.v_scale8[group_idx] = (uint8_t)scale_byte;
+                    cv.v_zero16[group_idx] = float_to_bf16(zero);
+                }
             }
         }
     }
@@ -467,12 +519,19 @@ __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int6
         if (which == 0) key_code_pos(D, BITS, tt, c, word, shift);
         else value_code_pos(D, BITS, tt, c, word, shift);
         if (codes) codes[((int64_t)head * count + i) * D + c] = (uint8_t)((base[word] >> shift) & ((1u << BITS) - 1u));
-        if (c == 0) {
-            const int64_t mi = (int64_t)head * cv.cap_tiles * kTileTokens + t;
-            if (scales) scales[(int64_t)head * count + i] = which == 0 ? cv.k_scale[mi] : cv.v_scale[mi];
-            if (zeros)
-                zeros[(int64_t)head * count + i] =
-                    which == 0 ? -cv.k_negzero[mi] - code_offset(BITS) : cv.v_zero_off[mi] - code_offset(BITS);
+        const int64_t mi = (int64_t)head * cv.cap_tiles * kTileTokens + t;
+        if (cv.meta_format == KVQ_META_FP32) {
+            if (c == 0) {
+                if (scales) scales[(int64_t)head * count + i] = which == 0 ? cv.k_scale[mi] : cv.v_scale[mi];
+                if (zeros)
+                    zeros[(int64_t)head * count + i] =
+                        which == 0 ? -cv.k_negzero[mi] - code_offset(BITS) : cv.v_zero_off[mi] - code_offset(BITS);
+            }
+        } else if (c % cv.group_size == 0) {
+            const int G = D / cv.group_size, g = c / cv.group_size;
+            const int64_t gi = mi * G + g, oi = ((int64_t)head * count + i) * G + g;
+            if (scales) scales[oi] = e4m3_to_float(which == 0 ? cv.k_scale8[gi] : cv.v_scale8[gi]);
+            if (zeros) zeros[oi] = bf16_to_float(which == 0 ? cv.k_zero16[gi] : cv.v_zero16[gi]);
         }
     }
 }
@@ -484,12 +543,21 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
     const int64_t first_tile = old_len / kTileTokens;
     const int64_t last_tile = (old_len + n - 1) / kTileTokens;
     const dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)cv.num_heads);
-    if constexpr (D == 128)
-        hipLaunchKernelGGL((quantize_append_kernel128<BITS, T>), grid, dim3(256), 0, stream, cv,
-                           static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
-    else
-        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, T>), grid, dim3(256), 0, stream, cv,
-                           static_cast<const T *>(k), static_cast<const T *>(v), old_len, n, st, sh);
+    const T *kp = static_cast<const T *>(k), *vp = static_cast<const T *>(v);
+    if (cv.meta_format == KVQ_META_FP8_BF16) {
+        if (cv.group_size == 32)
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 32, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+        else if (cv.group_size == 64)
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 64, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+        else if constexpr (D == 128)
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 128, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+        else
+            return hipErrorInvalidValue;
+    } else if constexpr (D == 128) {
+        hipLaunchKernelGGL((quantize_append_kernel128<BITS, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+    } else {
+        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+    }
     return hipGetLastError();
 }
 

@@ -25,9 +25,11 @@ def to_dev(x: np.ndarray, io_dtype: str) -> torch.Tensor:
     return t.to(torch.bfloat16) if io_dtype == "bf16" else t
 
 
-def make_cache(w: wl.Workload, capacity: int, heads: int = None) -> B.Cache:
+def make_cache(w: wl.Workload, capacity: int, heads: int = None, group: int = None, fp8_meta: bool = False) -> B.Cache:
     io = B.KVQ_BF16 if w.io_dtype == "bf16" else B.KVQ_FP32
-    return B.Cache(B.make_desc(w.num_heads if heads is None else heads, w.head_dim, w.bits, capacity, io), DEV)
+    meta = B.KVQ_META_FP8_BF16 if fp8_meta else B.KVQ_META_FP32
+    return B.Cache(B.make_desc(w.num_heads if heads is None else heads, w.head_dim, w.bits, capacity, io,
+                               group_size=group, meta_format=meta), DEV)
 
 
 def export_np(cache: B.Cache, which: int, start: int = 0, count: int = None):
@@ -43,18 +45,21 @@ def assert_quantized_equal(cache: B.Cache, k: np.ndarray, v: np.ndarray, heads=N
     n = k.shape[0]
     hs = list(range(cache.desc.num_heads)) if heads is None else list(heads)
     bits = cache.desc.bits
+    fp8_meta = cache.desc.meta_format == B.KVQ_META_FP8_BF16
+    group = cache.desc.group_size
     for which, x in ((0, k), (1, v)):
         codes, scales, zeros = export_np(cache, which, start, n)
+        scales, zeros = scales.reshape(scales.shape[0], n, -1), zeros.reshape(zeros.shape[0], n, -1)
         for j, h in enumerate(hs):
-            oc, osc, oz = oracle.quantize(x[:, j, :].astype(np.float64), bits)
+            oc, osc, oz = oracle.quantize(x[:, j, :].astype(np.float64), bits, group, True, fp8_meta)
             assert np.array_equal(codes[h], oc), "codes differ: tensor %d head %d (%d elements)" % (
                 which, h, int(np.sum(codes[h] != oc)))
-            bad = np.nonzero(scales[h].view(np.uint32) != osc[:, 0].view(np.uint32))[0]
+            bad = np.nonzero(np.any(scales[h].view(np.uint32) != osc.view(np.uint32), axis=1))[0]
             assert bad.size == 0, "scales differ: tensor %d head %d rows %s: %s vs %s" % (
-                which, h, bad[:8], scales[h][bad[:8]], osc[bad[:8], 0])
+                which, h, bad[:8], scales[h][bad[:8]], osc[bad[:8]])
             # zero-points are integers; +0 and -0 are the same zero-point
-            bad = np.nonzero(zeros[h] != oz[:, 0])[0]
-            assert bad.size == 0, "zero-points differ at rows %s: %s vs %s" % (bad[:8], zeros[h][bad[:8]], oz[bad[:8], 0])
+            bad = np.nonzero(np.any(zeros[h] != oz, axis=1))[0]
+            assert bad.size == 0, "zero-points differ at rows %s: %s vs %s" % (bad[:8], zeros[h][bad[:8]], oz[bad[:8]])
 
 
 def run_gpu_attention(cache, q, k_cur, v_cur, io_dtype, cache_start=0, cache_len=None, correction=1,

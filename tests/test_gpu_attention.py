@@ -151,6 +151,33 @@ def test_large_zero_points(P, bits):
         P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "large zero-points int%d" % bits)
 
 
+@pytest.mark.parametrize("correction", [1, 0])
+@pytest.mark.parametrize("bits,group", [(2, 32), (2, 64), (4, 32), (2, 128)])
+def test_group_wise_fp8_metadata(P, bits, group, correction):
+    """The paper's default storage format: per-group FP8-E4M3 scale and BF16 zero-point; the correction is
+    the per-group sum with the group norms of the rotated query (vector kernel)."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads, n_cached, n_cur, m = 2, 1000, 200, 160
+    cache = P.make_cache(w, n_cached, heads=heads, group=group, fp8_meta=True)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(1.5))
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction, group=group, fp8_meta=True)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction)
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d int%d" % (group, bits))
+    if correction:
+        off, mass_off, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 0, group=group, fp8_meta=True)
+        assert np.max(np.abs(mass_ref - mass_off)) > 1e-3      # the correction is visible at this size
+    # a window inside the cache
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc[37:901], vc[37:901], kr, vr, bits, correction, group=group,
+                                              fp8_meta=True)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=37, cache_len=864, correction=correction)
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d window" % group)
+
+
 def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None):
     """Full-size GPU run as the benchmark launches it; oracle on sampled heads x sampled rows."""
     import oracle

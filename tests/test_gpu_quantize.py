@@ -122,3 +122,42 @@ def test_capacity_and_argument_errors(P):
         B.kvq_cache_truncate(cache, 41)
     B.kvq_cache_reset(cache)
     assert len(cache) == 0
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("group", [32, 64, 128])
+def test_fp8_metadata_groups_bit_exact(P, bits, group):
+    """Group-wise quantization with FP8-E4M3 scales and BF16 zero-points: codes, stored scales and stored
+    zero-points equal the oracle's, for appends that start and end inside a tile."""
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads = 3
+    cache = P.make_cache(w, 300, heads=heads, group=group, fp8_meta=True)
+    assert B.kvq_cache_bytes(cache.desc) == 2 * heads * 320 * (128 * bits // 8 + 3 * (128 // group))
+    k, v = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=300)
+    # widen the dynamic range so that scales land in many binades, including E4M3 subnormals
+    k = wl.round_to_bf16(k * np.exp2(np.arange(300) % 19 - 12).astype(np.float32)[:, None, None])
+    pos = 0
+    for n in (45, 1, 130, 124):
+        B.kvq_quantize_append(cache, P.to_dev(k[pos:pos + n], "bf16"), P.to_dev(v[pos:pos + n], "bf16"))
+        pos += n
+    P.assert_quantized_equal(cache, k, v)
+
+
+def test_fp8_metadata_head_dim_64(P):
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["tiny"]
+    cache = P.make_cache(w, 256, group=32, fp8_meta=True)
+    k, v = wl.chunk_kv(w, 0, n_tokens=256)
+    B.kvq_quantize_append(cache, P.to_dev(k, w.io_dtype), P.to_dev(v, w.io_dtype))
+    P.assert_quantized_equal(cache, k, v)
+
+
+def test_fp8_metadata_descriptor_errors(P):
+    from paper_2605_26266_amd import binding as B
+    bad = [B.make_desc(2, 128, 2, 64, group_size=32),                                    # groups need the FP8 format
+           B.make_desc(2, 128, 2, 64, group_size=16, meta_format=B.KVQ_META_FP8_BF16),
+           B.make_desc(2, 64, 2, 64, group_size=128, meta_format=B.KVQ_META_FP8_BF16),
+           B.make_desc(2, 128, 2, 64, meta_format=7)]
+    for d in bad:
+        assert B.kvq_cache_bytes(d) == 0

@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--workload", default="large", choices=["small", "mid", "large", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=8, help="heads (all query rows each) given to the CPU oracle")
+    ap.add_argument("--meta", default="fp32", choices=["fp32", "fp8"],
+                    help="per-token metadata format of the cache: fp32 scale + zero-point (default, the headline "
+                         "configuration) or FP8-E4M3 scale + BF16 zero-point (2.19 bits per element at INT2)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warmup, run a plain elementwise kernel over a 1 GiB buffer three times "
                          "(dst = src + 1: reads 1 GiB, writes 1 GiB; outside the timed region): the yardstick "
@@ -140,7 +143,7 @@ def run_stream(args, torch, B, wl):
         "per_chunk_latency_ms": [float(a + b) for a, b in zip(t_q, t_a)],
         "attention_tflops": att_tf,
         "pct_mfma_peak": 100.0 * att_tf / MFMA_PEAK_TFLOPS,
-        "roofline": {"kernel": "attention_mfma_kernel<2, true>", "bound": "mfma", "achieved": att_tf,
+        "roofline": {"kernel": "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false"), "bound": "mfma", "achieved": att_tf,
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": att_tf / MFMA_PEAK_TFLOPS, "traffic": None},
     }
 
@@ -171,7 +174,8 @@ def main():
         return torch.from_numpy(x).to(dev).to(torch.bfloat16)
 
     # ---- resident inputs: the cache filled with chunks 0..n-2, chunk n-1 kept in bf16 for the timed append
-    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16), dev)
+    meta = B.KVQ_META_FP8_BF16 if args.meta == "fp8" else B.KVQ_META_FP32
+    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16, meta_format=meta), dev)
     for c in range(n_cached - 1):
         k, v = wl.chunk_kv(w, c)
         B.kvq_quantize_append(cache, up(k), up(v))
@@ -229,6 +233,7 @@ def main():
     t_off = np.median([p[1].elapsed_time(p[2]) for p in pair])
 
     flop = w.attention_flop
+    q_bytes = w.quantize_bytes(meta_bytes=3 if args.meta == "fp8" else 8)
     att_ms = float(np.mean(t_att))
     quant_ms = float(np.mean(t_quant))
     att_tflops = flop / (att_ms * 1e-3) / 1e12
@@ -246,19 +251,20 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "%s: %d heads, head_dim %d, chunk %d tokens, %d cached chunks (%d tokens) INT%d "
-                               "per-token asymmetric after Hadamard rotation, correction on"
-                               % (w.name, w.num_heads, w.head_dim, w.chunk_tokens, n_cached, w.cached_tokens, w.bits),
+                               "per-token asymmetric after Hadamard rotation, %s metadata, correction on"
+                               % (w.name, w.num_heads, w.head_dim, w.chunk_tokens, n_cached, w.cached_tokens, w.bits,
+                                  "FP8-E4M3/BF16" if args.meta == "fp8" else "fp32"),
                    "step": "quantize_append(1 chunk) + chunk_attention"},
         "attention_ms": att_ms,
         "attention_tflops": att_tflops,
         "pct_mfma_peak": 100.0 * att_tflops / MFMA_PEAK_TFLOPS,
         "quantize_ms": quant_ms,
-        "quantize_gb_per_s": w.quantize_bytes() / (quant_ms * 1e-3) / 1e9,
-        "quantize_pct_hbm_peak": 100.0 * w.quantize_bytes() / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "quantize_gb_per_s": q_bytes / (quant_ms * 1e-3) / 1e9,
+        "quantize_pct_hbm_peak": 100.0 * q_bytes / (quant_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "correction_overhead_pct": 100.0 * (t_on / t_off - 1.0),
         "attention_ms_uncorrected": float(t_off),
         "roofline": {
-            "kernel": "attention_mfma_kernel<2, true>",
+            "kernel": "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false"),
             "bound": "mfma",
             "achieved": att_tflops,
             "peak": MFMA_PEAK_TFLOPS,

@@ -268,7 +268,8 @@ template <int N, typename F> __device__ inline void static_for(F &&f)
     }
 }
 
-template <int BITS, bool CORR>
+// FP8META: the cache holds one FP8 E4M3 scale and one BF16 zero-point per token instead of two floats.
+template <int BITS, bool CORR, bool FP8META>
 __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
 {
     using St = Stage<BITS>;
@@ -515,13 +516,25 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             int64_t tok = tile0 * kTileTokens + ld_key;
             pre_valid = tok >= cs && tok < ce;
             tok = tok < cap_tokens ? tok : cap_tokens - 1;
-            if (ld_half == 0) {
-                pre_a = cv.k_negzero[meta0 + tok];
-                pre_b = cv.k_scale[meta0 + tok];
-            } else {
-                pre_a = cv.k_scale[meta0 + tok];
-                pre_b = cv.v_scale[meta0 + tok];
-                pre_c = cv.v_zero_off[meta0 + tok];
+            if constexpr (!FP8META) {
+                if (ld_half == 0) {
+                    pre_a = cv.k_negzero[meta0 + tok];
+                    pre_b = cv.k_scale[meta0 + tok];
+                } else {
+                    pre_a = cv.k_scale[meta0 + tok];
+                    pre_b = cv.v_scale[meta0 + tok];
+                    pre_c = cv.v_zero_off[meta0 + tok];
+                }
+            } else {   // FP8 E4M3 scale, BF16 zero-point, one pair per token
+                const float ks = e4m3_to_float(cv.k_scale8[meta0 + tok]);
+                if (ld_half == 0) {
+                    pre_a = -(bf16_val(cv.k_zero16[meta0 + tok]) + Unpack<BITS>::kStoredOffset);
+                    pre_b = ks;
+                } else {
+                    pre_a = ks;
+                    pre_b = e4m3_to_float(cv.v_scale8[meta0 + tok]);
+                    pre_c = bf16_val(cv.v_zero16[meta0 + tok]) + Unpack<BITS>::kStoredOffset;
+                }
             }
         };
         auto commit = [&](int stage) {
@@ -1081,10 +1094,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     }
 }
 
-template <int BITS, bool CORR> hipError_t launch(const AttentionArgs &a, hipStream_t stream)
+template <int BITS, bool CORR, bool FP8META> hipError_t launch(const AttentionArgs &a, hipStream_t stream)
 {
     static bool configured = false;  // per instantiation; the attribute is a property of the kernel
-    const void *fn = reinterpret_cast<const void *>(&attention_mfma_kernel<BITS, CORR>);
+    const void *fn = reinterpret_cast<const void *>(&attention_mfma_kernel<BITS, CORR, FP8META>);
     if (!configured) {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<BITS>());
         if (e != hipSuccess) return e;
@@ -1093,7 +1106,7 @@ template <int BITS, bool CORR> hipError_t launch(const AttentionArgs &a, hipStre
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
+    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR, FP8META>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
                        a, row_blocks);
     return hipGetLastError();
 }
@@ -1103,9 +1116,13 @@ template <int BITS, bool CORR> hipError_t launch(const AttentionArgs &a, hipStre
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream)
 {
     if (a.cv.head_dim != D || a.cv.io_dtype != KVQ_BF16) return hipErrorInvalidValue;
+    if (a.cv.meta_format != KVQ_META_FP32 && a.cv.group_size != D) return hipErrorInvalidValue;
     if (a.cache_len > (int64_t)0x3fffffff * kTileTokens) return hipErrorInvalidValue;
-    if (a.cv.bits == 2) return a.correction ? launch<2, true>(a, stream) : launch<2, false>(a, stream);
-    if (a.cv.bits == 4) return a.correction ? launch<4, true>(a, stream) : launch<4, false>(a, stream);
+    const bool fp8 = a.cv.meta_format == KVQ_META_FP8_BF16;
+    if (a.cv.bits == 2 && !fp8) return a.correction ? launch<2, true, false>(a, stream) : launch<2, false, false>(a, stream);
+    if (a.cv.bits == 4 && !fp8) return a.correction ? launch<4, true, false>(a, stream) : launch<4, false, false>(a, stream);
+    if (a.cv.bits == 2 && fp8) return a.correction ? launch<2, true, true>(a, stream) : launch<2, false, true>(a, stream);
+    if (a.cv.bits == 4 && fp8) return a.correction ? launch<4, true, true>(a, stream) : launch<4, false, true>(a, stream);
     return hipErrorInvalidValue;
 }
 

@@ -57,11 +57,12 @@ class Workload:
         m = self.chunk_tokens
         return 4.0 * self.num_heads * m * (self.cached_tokens + m) * self.head_dim
 
-    def quantize_bytes(self, n_tokens: Optional[int] = None) -> float:
-        """Bytes one append moves: K and V read once, codes + (scale, zero) written once."""
+    def quantize_bytes(self, n_tokens: Optional[int] = None, meta_bytes: int = 8) -> float:
+        """Bytes one append moves: K and V read once, codes + (scale, zero) written once.
+        meta_bytes per token and tensor: 8 (fp32 pair) or 3 per group (FP8 scale + BF16 zero-point)."""
         n = self.chunk_tokens if n_tokens is None else n_tokens
         elt = 2 if self.io_dtype == "bf16" else 4
-        per_row = self.head_dim * elt + self.head_dim * self.bits // 8 + 8
+        per_row = self.head_dim * elt + self.head_dim * self.bits // 8 + meta_bytes
         return 2.0 * n * self.num_heads * per_row
 
     def with_bits(self, bits: int) -> "Workload":

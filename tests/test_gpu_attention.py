@@ -166,8 +166,9 @@ def test_group_wise_fp8_metadata(P, bits, group, correction):
     kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
     q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(1.5))
     ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction, group=group, fp8_meta=True)
-    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction)
-    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d int%d" % (group, bits))
+    for fp32_kernel in ((False,) if group != 128 else (False, True)):   # per token: matrix cores by default
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction, fp32_kernel=fp32_kernel)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d int%d" % (group, bits))
     if correction:
         off, mass_off, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 0, group=group, fp8_meta=True)
         assert np.max(np.abs(mass_ref - mass_off)) > 1e-3      # the correction is visible at this size

@@ -748,9 +748,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             uint32_t off = lo_off;
             asm volatile("" : "+v"(off));
             const uint32_t *qlo = q_stage + off;
-            u32x4 lo_cur[kRB], lo_nxt[kRB];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords);
+            u32x4 lo_cur[kRB], lo_nxt[kRB], kop_prev;
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
@@ -775,11 +773,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             KVQ_CHUNK_FENCE();
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
-                if constexpr (SLAB < 7) {   // next slab's low query parts
+                // This slab's low query parts are requested now and multiplied one chunk later, so that no
+                // MFMA of the iteration waits for LDS: the high parts and the key codes are in registers.
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb)
-                        lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * (SLAB + 1));
-                }
+                for (int rb = 0; rb < kRB; ++rb)
+                    lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
                 if constexpr (SLAB == 5) {  // value codes and key scales for the second half of the iteration
                     const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
 #pragma unroll
@@ -797,13 +795,18 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const u32x4 kop = key_operand<BITS, SLAB>(pf.kw, uc);
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+                if constexpr (SLAB >= 1) {
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, lo_cur[rb], sn[rb]);
-                if constexpr (SLAB >= 1) exp_chunk(IntC<SLAB - 1>{});
+                    for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                    exp_chunk(IntC<SLAB - 1>{});
+                }
+                kop_prev = kop;
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
                 KVQ_CHUNK_FENCE();
             });
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
             exp_chunk(IntC<7>{});
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
@@ -815,6 +818,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             lo_flag = lo_flags.x | lo_flags.y;
             // key codes of the tile after next (its stage has been opened at the top of this iteration)
             prefetch_keys(t + 2, pf);
+            KVQ_CHUNK_FENCE();   // the score accumulators are read after all of the above, not before
             float mx[kRB];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;

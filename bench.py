@@ -44,6 +44,9 @@ def parse():
     ap.add_argument("--meta", default="fp32", choices=["fp32", "fp8"],
                     help="per-token metadata format of the cache: fp32 scale + zero-point (default, the headline "
                          "configuration) or FP8-E4M3 scale + BF16 zero-point (2.19 bits per element at INT2)")
+    ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64],
+                    help="channels per (scale, zero-point) group; 0 = one group per token.  Groups of 32 or 64 use "
+                         "FP8-E4M3/BF16 metadata (2.75 / 2.375 bits per element at INT2)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="before the warmup, run a plain elementwise kernel over a 1 GiB buffer three times "
                          "(dst = src + 1: reads 1 GiB, writes 1 GiB; outside the timed region): the yardstick "
@@ -174,8 +177,12 @@ def main():
         return torch.from_numpy(x).to(dev).to(torch.bfloat16)
 
     # ---- resident inputs: the cache filled with chunks 0..n-2, chunk n-1 kept in bf16 for the timed append
+    if args.group:
+        args.meta = "fp8"
     meta = B.KVQ_META_FP8_BF16 if args.meta == "fp8" else B.KVQ_META_FP32
-    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16, meta_format=meta), dev)
+    n_groups = w.head_dim // args.group if args.group else 1
+    cache = B.Cache(B.make_desc(w.num_heads, w.head_dim, w.bits, w.cached_tokens, B.KVQ_BF16, meta_format=meta,
+                                group_size=args.group or None), dev)
     for c in range(n_cached - 1):
         k, v = wl.chunk_kv(w, c)
         B.kvq_quantize_append(cache, up(k), up(v))
@@ -233,7 +240,7 @@ def main():
     t_off = np.median([p[1].elapsed_time(p[2]) for p in pair])
 
     flop = w.attention_flop
-    q_bytes = w.quantize_bytes(meta_bytes=3 if args.meta == "fp8" else 8)
+    q_bytes = w.quantize_bytes(meta_bytes=3 * n_groups if args.meta == "fp8" else 8)
     att_ms = float(np.mean(t_att))
     quant_ms = float(np.mean(t_quant))
     att_tflops = flop / (att_ms * 1e-3) / 1e12
@@ -251,8 +258,9 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "%s: %d heads, head_dim %d, chunk %d tokens, %d cached chunks (%d tokens) INT%d "
-                               "per-token asymmetric after Hadamard rotation, %s metadata, correction on"
+                               "%s asymmetric after Hadamard rotation, %s metadata, correction on"
                                % (w.name, w.num_heads, w.head_dim, w.chunk_tokens, n_cached, w.cached_tokens, w.bits,
+                                  "group-wise (g = %d)" % args.group if args.group else "per-token",
                                   "FP8-E4M3/BF16" if args.meta == "fp8" else "fp32"),
                    "step": "quantize_append(1 chunk) + chunk_attention"},
         "attention_ms": att_ms,
@@ -264,13 +272,14 @@ def main():
         "correction_overhead_pct": 100.0 * (t_on / t_off - 1.0),
         "attention_ms_uncorrected": float(t_off),
         "roofline": {
-            "kernel": "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false"),
+            "kernel": ("attention_mfma_group_kernel<2, true, %d>" % n_groups if args.group else
+                       "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false")),
             "bound": "mfma",
             "achieved": att_tflops,
             "peak": MFMA_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": att_tflops / MFMA_PEAK_TFLOPS,
-            "traffic": ATTENTION_TRAFFIC_BYTES_LARGE if w.name == "large" else None,
+            "traffic": ATTENTION_TRAFFIC_BYTES_LARGE if w.name == "large" and args.meta == "fp32" else None,
         },
     }
     if not args.no_cpu_baseline:

@@ -21,6 +21,7 @@ SOURCES = {
     "kvq_quantize.hip": ["-ffp-contract=off"],
     "kvq_attention_simt.hip": [],
     "kvq_attention_mfma.hip": [],
+    "kvq_attention_mfma_group.hip": [],
 }
 
 

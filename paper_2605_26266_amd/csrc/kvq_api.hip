@@ -179,7 +179,10 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
                              d.group_size == d.head_dim;   // one (scale, zero-point) per token, either format
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const hipError_t e = matrix_path ? kvq::launch_attention_mfma(a, s) : kvq::launch_attention_simt(a, s);
+    const bool group_matrix_path = !force_vector && kvq::attention_mfma_group_supported(cache->view);
+    const hipError_t e = matrix_path         ? kvq::launch_attention_mfma(a, s)
+                         : group_matrix_path ? kvq::launch_attention_mfma_group(a, s)
+                                             : kvq::launch_attention_simt(a, s);
     return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
 }
 

@@ -124,5 +124,8 @@ struct AttentionArgs {
 };
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream);
+// Matrix-core kernel for caches with several FP8/BF16 (scale, zero-point) groups per token.
+bool attention_mfma_group_supported(const CacheView &cv);
+hipError_t launch_attention_mfma_group(const AttentionArgs &a, hipStream_t stream);
 
 }  // namespace kvq

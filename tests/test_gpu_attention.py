@@ -166,7 +166,7 @@ def test_group_wise_fp8_metadata(P, bits, group, correction):
     kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
     q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(1.5))
     ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction, group=group, fp8_meta=True)
-    for fp32_kernel in ((False,) if group != 128 else (False, True)):   # per token: matrix cores by default
+    for fp32_kernel in (False, True):   # default dispatch (matrix cores where supported) and the vector kernel
         out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction, fp32_kernel=fp32_kernel)
         P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d int%d" % (group, bits))
     if correction:
@@ -179,13 +179,13 @@ def test_group_wise_fp8_metadata(P, bits, group, correction):
     P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d window" % group)
 
 
-def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None):
+def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None, group=None):
     """Full-size GPU run as the benchmark launches it; oracle on sampled heads x sampled rows."""
     import oracle
     from paper_2605_26266_amd import binding as B, workloads as wl
     w = wl.WORKLOADS[name].with_bits(bits)
     n_chunks = w.cached_chunks if cached_chunks is None else cached_chunks
-    cache = P.make_cache(w, n_chunks * w.chunk_tokens)
+    cache = P.make_cache(w, n_chunks * w.chunk_tokens, group=group, fp8_meta=group is not None)
     ks, vs = [], []
     for c in range(n_chunks):
         k, v = wl.chunk_kv(w, c)
@@ -197,7 +197,8 @@ def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None
     q = wl.chunk_q(w)
     rows = wl.sample_rows(w, n_rows)
     out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction)
-    ref, mass_ref, _ = oracle.chunk_attention(q[rows][:, heads], kc, vc, kr[:, heads], vr[:, heads], bits, correction)
+    ref, mass_ref, _ = oracle.chunk_attention(q[rows][:, heads], kc, vc, kr[:, heads], vr[:, heads], bits, correction,
+                                              group=group, fp8_meta=group is not None)
     return P.assert_attention_close(out[rows][:, heads], mass[heads][:, rows], ref, mass_ref, P.TOL_OUT_BF16,
                                     "%s int%d" % (name, bits))
 
@@ -206,6 +207,13 @@ def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None
 def test_mid_sampled_rows(P, bits):
     err = _sampled_case(P, "mid", bits, 48, [0, 23])
     print("mid int%d: max err %.2e" % (bits, err))
+
+
+@pytest.mark.parametrize("group", [32, 64])
+def test_mid_group_wise_sampled_rows(P, group):
+    """The paper's default format (INT2, FP8/BF16 metadata per 32 channels) at the mid shape on the matrix
+    cores, and g = 64."""
+    _sampled_case(P, "mid", 2, 48, [0, 23], group=group)
 
 
 @pytest.mark.parametrize("correction", [1, 0])

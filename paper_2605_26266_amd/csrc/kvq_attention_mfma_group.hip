@@ -390,20 +390,21 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 ks_pair[j] = sf | (sf << 16);
             }
             const uint16_t bias = pre_valid ? (uint16_t)0 : bf16_bits(kMaskBias);
+            // ld_half is uniform over a wave: each half builds only its own eight slots of every operand
+            auto build_cops = [&](auto h_) {
+                constexpr int H2 = decltype(h_)::value;
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                uint32_t w[2][4];
-#pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        w[h2][k] = (uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * h2 + 2 * k) |
-                                   ((uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * h2 + 2 * k + 1) << 16);
-                u32x4 cop;
-                cop.x = ld_half ? w[1][0] : w[0][0]; cop.y = ld_half ? w[1][1] : w[0][1];
-                cop.z = ld_half ? w[1][2] : w[0][2]; cop.w = ld_half ? w[1][3] : w[0][3];
-                *reinterpret_cast<u32x4 *>(buf + St::kCop + ((tl * NC + c) * 64 + ld_half * 32 + r) * 4) = cop;
-            }
+                for (int c = 0; c < NC; ++c) {
+                    u32x4 cop;
+                    cop.x = (uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 0) | ((uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 1) << 16);
+                    cop.y = (uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 2) | ((uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 3) << 16);
+                    cop.z = (uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 4) | ((uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 5) << 16);
+                    cop.w = (uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 6) | ((uint32_t)key_slot<G>(kg, bias, 16 * c + 8 * H2 + 7) << 16);
+                    *reinterpret_cast<u32x4 *>(buf + St::kCop + ((tl * NC + c) * 64 + H2 * 32 + r) * 4) = cop;
+                }
+            };
+            if (ld_half == 0) build_cops(IntC<0>{});
+            else build_cops(IntC<1>{});
             if (ld_half == 0) {
 #pragma unroll
                 for (int j = 0; j < G; ++j) buf[St::kKs + (tl * 32 + r) * G + j] = ks_pair[j];
@@ -500,11 +501,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             return z;
         };
         // tau of tile t from its probabilities: rows 4 hh .. 4 hh + 3 of the result belong to this lane half.
-        auto add_tau = [&](int t, const u32x4 (&pop)[kRB][2]) {
+        auto load_tau_operand = [&](int t, u32x4 (&top)[2]) {
             const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
             const uint32_t *src = buf + St::kTau + ((((t & 3) * 2) * 2 + hh) * 8 + (n & 7)) * 4;
-            const u32x4 t0 = *reinterpret_cast<const u32x4 *>(src);
-            const u32x4 t1 = *reinterpret_cast<const u32x4 *>(src + 2 * 8 * 4);
+            top[0] = *reinterpret_cast<const u32x4 *>(src);
+            top[1] = *reinterpret_cast<const u32x4 *>(src + 2 * 8 * 4);
+        };
+        auto add_tau = [&](const u32x4 (&top)[2], const u32x4 (&pop)[kRB][2]) {
+            const u32x4 t0 = top[0], t1 = top[1];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
                 f32x16 tt = mfma_f16(t0, pop[rb][0], zero16());
@@ -595,7 +599,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_f16(v1, pop[rb][1], o[B][rb]);
             });
-            add_tau(t, pop);
+            u32x4 top[2];
+            load_tau_operand(t, top);
+            add_tau(top, pop);
         };
         // One steady-state iteration: score MFMAs of tile t+1 next to the exponentials of tile t, then the
         // P*V MFMAs of tile t next to the reference subtraction of tile t+1, then tau of tile t.
@@ -617,6 +623,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             float lsum[kRB] = {};
             uint32_t pw[kRB][8];
             uint32_t vw[WPL];
+            uint32_t vs_cur[8], vs_nxt[8];
+            u32x4 top[2];
             auto exp_chunk = [&](auto c_) {
                 constexpr int C = decltype(c_)::value;
                 constexpr int RB = (C * kRB) / 8, I0 = (C * kRB) % 8;
@@ -635,6 +643,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 for (int rb = 0; rb < kRB; ++rb)
                     lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
                 if constexpr (SLAB == 5) load_value_words(t, vw);
+                if constexpr (SLAB == 7) load_value_steps(bufc, t & 3, 0, vs_cur);
                 const u32x4 kop = scaled_key_operand(s_, pf.kw, ks);
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
@@ -664,14 +673,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
             static_for<4>([&](auto b_) {
                 constexpr int B = decltype(b_)::value;
-                uint32_t vs[8];
-                load_value_steps(bufc, t & 3, B, vs);
-                const u32x4 v0 = scaled_value_operand(b_, IntC<0>{}, vw, vs);
-                const u32x4 v1 = scaled_value_operand(b_, IntC<1>{}, vw, vs);
+                if constexpr (B < 3) load_value_steps(bufc, t & 3, B + 1, vs_nxt);   // next block's steps
+                if constexpr (B == 0) load_tau_operand(t, top);
+                const u32x4 v0 = scaled_value_operand(b_, IntC<0>{}, vw, vs_cur);
+                const u32x4 v1 = scaled_value_operand(b_, IntC<1>{}, vw, vs_cur);
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_f16(v0, pop[rb][0], o[B][rb]);
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_f16(v1, pop[rb][1], o[B][rb]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) vs_cur[i] = vs_nxt[i];
                 constexpr int RB = (B * 4 * kRB) / 16, V0 = (B * 4 * kRB) % 16;
 #pragma unroll
                 for (int v = V0; v < V0 + 4 * kRB; ++v) e[RB][v] = sn[RB][v] - m_ref[RB];
@@ -679,7 +690,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
                 KVQ_CHUNK_FENCE();
             });
-            add_tau(t, pop);
+            add_tau(top, pop);
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(mx[rb]);
         };

@@ -129,7 +129,9 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
  *
  * q, out: device [m][num_heads][head_dim]; k_cur, v_cur: device [n_cur][num_heads][head_dim];
  * all in io_dtype with the same strides.  mass_cached: device float [num_heads][m] or NULL.
- * softmax_scale == 0 selects 1/sqrt(head_dim).  correction: 0 off, 1 Taylor.
+ * softmax_scale == 0 selects 1/sqrt(head_dim).  correction: 0 off, 1 Taylor (Eq. 13 / 15), 2 exact form
+ * b_mi = sum_c log(sinh(a_c)/a_c), a_c = softmax_scale * (Hn q_m)_c * step_i,g(c) / 2 (Eq. 12; a diagnostic
+ * mode that always runs the fp32 vector kernel).
  * cache_len == 0 (first chunk) and n_cur == 0 are allowed, not both; m == 0 is a no-op.
  * `out` must not alias the inputs.
  */

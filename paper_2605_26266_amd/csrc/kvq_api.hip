@@ -147,7 +147,7 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     if (!cache || m < 0 || n_cur < 0 || cache_len < 0 || cache_start < 0) return KVQ_ERR_INVALID_ARG;
     if (cache_start + cache_len > cache->len) return KVQ_ERR_INVALID_ARG;
     if (cache_len == 0 && n_cur == 0) return KVQ_ERR_INVALID_ARG;
-    if (correction != 0 && correction != 1) return KVQ_ERR_INVALID_ARG;
+    if (correction < 0 || correction > 2) return KVQ_ERR_INVALID_ARG;
     if (!(softmax_scale >= 0.0f) || !(softmax_scale < 3.0e38f)) return KVQ_ERR_INVALID_ARG;
     if (m == 0) return KVQ_OK;
     const kvq_cache_desc &d = cache->desc;
@@ -176,6 +176,8 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.correction = correction;
     a.out = out;
     a.mass_cached = mass_cached;
+    // the exact (sinh) correction is a diagnostic mode: vector kernel only
+    force_vector = force_vector || correction == 2;
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
                              d.group_size == d.head_dim;   // one (scale, zero-point) per token, either format
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -44,6 +44,18 @@ template <int D> __device__ inline float block_reduce(float v, float *scratch, i
     return r;
 }
 
+// log(sinh(x)/x), the log moment of uniform noise on one channel (Eq. 12 of the paper): a series where
+// the closed form would cancel, the overflow-free closed form elsewhere.
+__device__ inline float log_sinhc(float x)
+{
+    x = fabsf(x);
+    if (x < 0.5f) {
+        const float x2 = x * x;
+        return x2 * (1.0f / 6.0f + x2 * (-1.0f / 180.0f + x2 * (1.0f / 2835.0f + x2 * (-1.0f / 37800.0f + x2 * (1.0f / 467775.0f)))));
+    }
+    return x + log1pf(-expf(-2.0f * x)) - logf(2.0f * x);
+}
+
 template <int D, int BITS, typename T>
 __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
 {
@@ -80,7 +92,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
         if (c < G) {
             float nu = 0.0f;
             for (int i = 0; i < group; ++i) nu += scratch[c * group + i];
-            corr_g[c] = a.correction ? sigma * sigma * nu * (1.0f / 24.0f) : 0.0f;
+            corr_g[c] = a.correction == 1 ? sigma * sigma * nu * (1.0f / 24.0f) : 0.0f;
         }
         __syncthreads();
     }
@@ -116,6 +128,8 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
                     const float scale = scale_g[ch / group], zero = zero_g[ch / group];   // ch, ch + 1: same group
                     dot = fmaf(q_rot[ch], (c0 - zero) * scale, dot);
                     dot = fmaf(q_rot[ch + 1], (c1 - zero) * scale, dot);
+                    if (a.correction == 2)   // exact form: sum over channels of log(sinh a / a), a = sigma q~_c step / 2
+                        b += log_sinhc(0.5f * sigma * q_rot[ch] * scale) + log_sinhc(0.5f * sigma * q_rot[ch + 1] * scale);
                 }
             }
         }

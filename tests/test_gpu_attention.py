@@ -179,6 +179,26 @@ def test_group_wise_fp8_metadata(P, bits, group, correction):
     P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "group %d window" % group)
 
 
+@pytest.mark.parametrize("group,fp8", [(None, False), (32, True)])
+def test_exact_correction_mode(P, group, fp8):
+    """correction = 2: the exact log-moment form (Eq. 12) on the vector kernel, against the oracle's; it
+    stays within the fourth-order term of the Taylor form."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, n_cached, n_cur, m = 2, 600, 100, 96
+    cache = P.make_cache(w, n_cached, heads=heads, group=group, fp8_meta=fp8)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(2.0))
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 2, group=group, fp8_meta=fp8)
+    tay, mass_tay, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1, group=group, fp8_meta=fp8)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=2)
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "exact correction")
+    assert 0 < np.max(np.abs(mass_ref - mass_tay)) < 0.05      # the two forms differ, slightly
+
+
 def _sampled_case(P, name, bits, n_rows, heads, correction=1, cached_chunks=None, group=None):
     """Full-size GPU run as the benchmark launches it; oracle on sampled heads x sampled rows."""
     import oracle
@@ -268,5 +288,5 @@ def test_argument_errors(P):
     with pytest.raises(B.KvqError):
         B.kvq_chunk_attention(cache, 0, 64, q, None, None, q)        # out aliases q
     with pytest.raises(B.KvqError):
-        B.kvq_chunk_attention(cache, 0, 64, q, None, None, out, correction=2)
+        B.kvq_chunk_attention(cache, 0, 64, q, None, None, out, correction=3)
     B.kvq_chunk_attention(cache, 0, 64, q[:0], None, None, out[:0])   # m == 0 is a no-op

@@ -89,12 +89,20 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
 /* Frees the host object only; the device storage stays with the caller. */
 void kvq_cache_destroy(kvq_cache *cache);
 
-/* Number of tokens appended so far (host-side counter; -1 for a null cache). */
+/* Number of live tokens (host-side counter; -1 for a null cache). */
 int64_t kvq_cache_len(const kvq_cache *cache);
 
-/* Forget every token / every token from new_len on (host-side counter only; 0 <= new_len <= len). */
+/* Forget every token / every token from new_len on (host-side counters only; 0 <= new_len <= len). */
 kvq_status kvq_cache_reset(kvq_cache *cache);
 kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len);
+
+/* Sliding window (the cached-chunk window of chunk-wise video generation): forget the n_tokens oldest
+ * tokens (0 <= n_tokens <= len; host-side counters only).  The storage is a ring of 32-token tiles, so the
+ * space is reused by later appends; positions in kvq_chunk_attention and kvq_cache_export count from the
+ * oldest live token.  An append fails with KVQ_ERR_CAPACITY when live and new tokens together touch more
+ * tiles than the storage has; with evictions and appends in multiples of 32 tokens that is exactly
+ * len + n_tokens > capacity_tokens. */
+kvq_status kvq_cache_evict(kvq_cache *cache, int64_t n_tokens);
 
 /*
  * Append one chunk: for each (token, head) the key and the value vector are rotated by the
@@ -117,7 +125,7 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
 
 /*
  * Corrected chunk attention.  For every head and query row m:
- *     cached key i in [cache_start, cache_start + cache_len):
+ *     cached key i in [cache_start, cache_start + cache_len), counted from the oldest live token:
  *         s_i = softmax_scale * (Hn q_m) . k^_i  -  b_mi,
  *         b_mi = correction ? softmax_scale^2 / 24 * sum_j step_ij^2 * ||(Hn q_m)_j||^2 : 0
  *         (j runs over the groups; per token this is softmax_scale^2 * step_i^2 * ||q_m||^2 / 24)

@@ -21,7 +21,7 @@ KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
 # Every symbol declared in include/kvq.h.
 EXPORTED = (
     "kvq_cache_bytes", "kvq_cache_create", "kvq_cache_destroy", "kvq_cache_len", "kvq_cache_reset",
-    "kvq_cache_truncate", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
+    "kvq_cache_truncate", "kvq_cache_evict", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
     "kvq_cache_export", "kvq_status_string", "kvq_version",
 )
 
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
     L.kvq_cache_len.restype = i64
     L.kvq_cache_reset.argtypes = [vp]
     L.kvq_cache_truncate.argtypes = [vp, i64]
+    L.kvq_cache_evict.argtypes = [vp, i64]
     L.kvq_quantize_append.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     att = [vp, i64, i64, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp, vp, vp]
     L.kvq_chunk_attention.argtypes = att
@@ -150,6 +151,10 @@ def kvq_cache_reset(cache: Cache) -> None:
 
 def kvq_cache_truncate(cache: Cache, new_len: int) -> None:
     _check(lib().kvq_cache_truncate(cache.handle, int(new_len)), "kvq_cache_truncate")
+
+
+def kvq_cache_evict(cache: Cache, n_tokens: int) -> None:
+    _check(lib().kvq_cache_evict(cache.handle, int(n_tokens)), "kvq_cache_evict")
 
 
 def _tok_head_strides(t: torch.Tensor):

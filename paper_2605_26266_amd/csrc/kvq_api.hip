@@ -8,7 +8,8 @@ struct kvq_cache {
     kvq_cache_desc desc;
     kvq::CacheView view;
     int64_t cap32;  // capacity rounded up to whole tiles
-    int64_t len;    // tokens appended so far
+    int64_t base;   // logical position of the oldest live token (the storage is a ring)
+    int64_t len;    // live tokens
 };
 
 namespace {
@@ -70,6 +71,7 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
     c->desc = *desc;
     c->cap32 = round_up_tile(desc->capacity_tokens);
     c->len = 0;
+    c->base = 0;
     const int64_t H = desc->num_heads;
     const int64_t code_bytes = H * c->cap32 * desc->head_dim * desc->bits / 8;  // multiple of 256
     const int64_t meta_bytes = H * c->cap32 * 4;                                // multiple of 128
@@ -111,6 +113,16 @@ kvq_status kvq_cache_reset(kvq_cache *cache)
 {
     if (!cache) return KVQ_ERR_INVALID_ARG;
     cache->len = 0;
+    cache->base = 0;
+    return KVQ_OK;
+}
+
+kvq_status kvq_cache_evict(kvq_cache *cache, int64_t n_tokens)
+{
+    if (!cache || n_tokens < 0 || n_tokens > cache->len) return KVQ_ERR_INVALID_ARG;
+    cache->base += n_tokens;
+    cache->len -= n_tokens;
+    if (cache->len == 0) cache->base = 0;   // an empty cache starts over at a tile boundary
     return KVQ_OK;
 }
 
@@ -131,7 +143,11 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
         !tensor_ok(v, stride_token, stride_head, d.head_dim, d.io_dtype))
         return KVQ_ERR_INVALID_ARG;
     if (n_tokens > d.capacity_tokens - cache->len) return KVQ_ERR_CAPACITY;
-    const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->len, n_tokens, stride_token,
+    // Ring storage: the tiles touched by the live tokens and the new ones must all be distinct.
+    const int64_t first_tile = cache->base / kvq::kTileTokens;
+    const int64_t last_tile = (cache->base + cache->len + n_tokens - 1) / kvq::kTileTokens;
+    if (last_tile - first_tile + 1 > cache->view.cap_tiles) return KVQ_ERR_CAPACITY;
+    const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->base + cache->len, n_tokens, stride_token,
                                                      stride_head, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return KVQ_ERR_HIP;
     cache->len += n_tokens;
@@ -163,8 +179,9 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
 
     kvq::AttentionArgs a;
     a.cv = cache->view;
-    a.cache_start = cache_start;
+    a.cache_start = cache->base + cache_start;
     a.cache_len = cache_len;
+    a.phys_tile_first = (a.cache_start / kvq::kTileTokens) % cache->view.cap_tiles;
     a.q = q;
     a.k_cur = k_cur;
     a.v_cur = v_cur;
@@ -214,7 +231,7 @@ kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, in
     if (!cache || (which != 0 && which != 1) || start < 0 || count < 0) return KVQ_ERR_INVALID_ARG;
     if (start + count > cache->len) return KVQ_ERR_INVALID_ARG;
     if (count == 0) return KVQ_OK;
-    const hipError_t e = kvq::launch_export(cache->view, which, start, count, codes, scales, zeros,
+    const hipError_t e = kvq::launch_export(cache->view, which, cache->base + start, count, codes, scales, zeros,
                                             static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
 }

@@ -312,17 +312,23 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
             const int64_t tile0 = t_first + (int64_t)stage * kStageTiles;
+            const int64_t phys_tile0 = a.phys_tile_first + (int64_t)stage * kStageTiles;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
                 const int g = tid + kThreads * it, vec = g % kCodeVecs;
-                int64_t tile = tile0 + vec / (16 * WPL);
-                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // never read past the storage
+                int64_t tile = phys_tile0 + vec / (16 * WPL);   // ring: at most two wraps (n_tiles <= cap_tiles + 1)
+                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
+                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
+                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // tiles past the window: any address inside the storage   // never read past the storage
                 const int64_t word = (head_tile0 + tile) * (64 * WPL) + (vec % (16 * WPL)) * 4;
                 pre_kv[it] = *reinterpret_cast<const u32x4 *>((g < kCodeVecs ? cv.k_codes : cv.v_codes) + word);
             }
             if (!ld_meta) return;
             int64_t tok = tile0 * kTileTokens + ld_key;
             pre_valid = tok >= cs && tok < ce;
+            tok = phys_tile0 * kTileTokens + ld_key;
+            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
+            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
             tok = tok < cap_tokens ? tok : cap_tokens - 1;
             if constexpr (!FP8META) {
                 if (ld_half == 0) {

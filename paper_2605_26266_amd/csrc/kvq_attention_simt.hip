@@ -101,7 +101,9 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     const uint32_t *k_head = cv.k_codes + (int64_t)head * cv.cap_tiles * tile_words(D, BITS);
     const uint32_t *v_head = cv.v_codes + (int64_t)head * cv.cap_tiles * tile_words(D, BITS);
 
-    auto cached_score = [&](int64_t t) -> float {
+    const int64_t cap_tokens = cv.cap_tiles * kTileTokens;
+    auto cached_score = [&](int64_t t_logical) -> float {
+        const int64_t t = t_logical % cap_tokens;   // position in the ring
         const uint32_t *tile = k_head + (t / kTileTokens) * tile_words(D, BITS);
         const int tt = (int)(t % kTileTokens);
         float scale_g[4], zero_g[4], b = 0.0f;
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
         __syncthreads();
         const int cnt = (int)((a.cache_len - base) < D ? (a.cache_len - base) : D);
         for (int jj = 0; jj < cnt; ++jj) {
-            const int64_t t = a.cache_start + base + jj;
+            const int64_t t = (a.cache_start + base + jj) % cap_tokens;
             int word, shift;
             value_code_pos(D, BITS, (int)(t % kTileTokens), c, word, shift);
             const uint32_t w = v_head[(t / kTileTokens) * tile_words(D, BITS) + word];

@@ -114,7 +114,8 @@ hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t 
 
 struct AttentionArgs {
     CacheView cv;
-    int64_t cache_start, cache_len;
+    int64_t cache_start, cache_len;   // logical token positions (the storage is a ring of cap_tiles tiles)
+    int64_t phys_tile_first;          // physical tile that holds logical token cache_start
     const void *q, *k_cur, *v_cur;
     int64_t m, n_cur, stride_token, stride_head;
     float softmax_scale;

@@ -136,9 +136,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
     const int row = threadIdx.x >> 3, l8 = threadIdx.x & 7;
     const int64_t t = tile_t0 + row;
     const bool valid = t >= lo_t && t < hi_t;
-    const int64_t meta_idx = (int64_t)head * cv.cap_tiles * kTileTokens + t;
-    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
-    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    // The storage is a ring of cap_tiles tiles per head: logical tile -> physical tile.
+    const int64_t ptile = tile % cv.cap_tiles;
+    const int64_t meta_idx = ((int64_t)head * cv.cap_tiles + ptile) * kTileTokens + row;
+    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + ptile) * (64 * WPL);
+    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + ptile) * (64 * WPL);
     const double norm = D == 64 ? 0.125 : 0.08838834764831845;  // 1/sqrt(d) rounded to double
 
 #pragma unroll 1
@@ -343,9 +345,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
     const int64_t t = tile_t0 + row;
     const bool valid = t >= lo_t && t < hi_t;
     const bool tail = t >= hi_t;
-    const int64_t meta_idx = (int64_t)head * cv.cap_tiles * kTileTokens + t;
-    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
-    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + tile) * (64 * WPL);
+    // The storage is a ring of cap_tiles tiles per head: logical tile -> physical tile.
+    const int64_t ptile = tile % cv.cap_tiles;
+    const int64_t meta_idx = ((int64_t)head * cv.cap_tiles + ptile) * kTileTokens + row;
+    uint32_t *k_tile = cv.k_codes + ((int64_t)head * cv.cap_tiles + ptile) * (64 * WPL);
+    uint32_t *v_tile = cv.v_codes + ((int64_t)head * cv.cap_tiles + ptile) * (64 * WPL);
     double *rowbuf = xpose[row];
 
     // Both loads are in flight before any arithmetic starts.
@@ -511,7 +515,7 @@ __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int6
     const int c = threadIdx.x;
     for (int64_t i = blockIdx.x; i < count; i += gridDim.x) {
         const int64_t t = start + i;
-        const int64_t tile = t / kTileTokens;
+        const int64_t tile = (t / kTileTokens) % cv.cap_tiles;   // physical tile of the ring
         const int tt = (int)(t % kTileTokens);
         const uint32_t *base = (which == 0 ? cv.k_codes : cv.v_codes) +
                                ((int64_t)head * cv.cap_tiles + tile) * tile_words(D, BITS);
@@ -519,7 +523,7 @@ __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int6
         if (which == 0) key_code_pos(D, BITS, tt, c, word, shift);
         else value_code_pos(D, BITS, tt, c, word, shift);
         if (codes) codes[((int64_t)head * count + i) * D + c] = (uint8_t)((base[word] >> shift) & ((1u << BITS) - 1u));
-        const int64_t mi = (int64_t)head * cv.cap_tiles * kTileTokens + t;
+        const int64_t mi = ((int64_t)head * cv.cap_tiles + tile) * kTileTokens + tt;
         if (cv.meta_format == KVQ_META_FP32) {
             if (c == 0) {
                 if (scales) scales[(int64_t)head * count + i] = which == 0 ? cv.k_scale[mi] : cv.v_scale[mi];

@@ -272,6 +272,51 @@ def test_stream_append_then_attend(P):
     assert len(cache) == w.cached_tokens
 
 
+@pytest.mark.parametrize("group,fp8", [(None, False), (32, True)])
+def test_sliding_window_ring(P, group, fp8):
+    """A cache with room for three 96-token chunks slides over nine chunks: evict the oldest, append the
+    next, attend to the window.  After the storage has wrapped, codes and attention still equal the
+    oracle's on the same logical window, for windows that start and end inside tiles too."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, chunk, window = 2, 96, 3
+    cache = P.make_cache(w, chunk * window, heads=heads, group=group, fp8_meta=fp8)
+    chunks = [wl.chunk_kv(w, c, heads=range(heads), n_tokens=chunk) for c in range(9)]
+    q = wl.chunk_q(w, heads=range(heads))[:80]
+    kr, vr = wl.chunk_kv(w, 20, heads=range(heads), n_tokens=40)
+    live = []
+    for c, (k, v) in enumerate(chunks):
+        if len(live) == window:
+            B.kvq_cache_evict(cache, chunk)
+            live.pop(0)
+        B.kvq_quantize_append(cache, P.to_dev(k, "bf16"), P.to_dev(v, "bf16"))
+        live.append((k, v))
+        assert len(cache) == chunk * len(live)
+        if c in (2, 4, 5, 8):
+            kc, vc = np.concatenate([x[0] for x in live]), np.concatenate([x[1] for x in live])
+            P.assert_quantized_equal(cache, kc, vc)
+            for (start, clen) in ((0, len(kc)), (17, len(kc) - 40)):
+                ref, mass_ref, _ = oracle.chunk_attention(q, kc[start:start + clen], vc[start:start + clen], kr, vr, 2, 1,
+                                                          group=group, fp8_meta=fp8)
+                for fp32_kernel in (False, True):
+                    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=start, cache_len=clen,
+                                                    fp32_kernel=fp32_kernel)
+                    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "ring chunk %d" % c)
+    # evictions that are not multiples of a tile: the next append must not touch a tile that is still live
+    B.kvq_cache_evict(cache, 50)
+    with pytest.raises(B.KvqError) as e:
+        B.kvq_quantize_append(cache, P.to_dev(chunks[0][0][:50], "bf16"), P.to_dev(chunks[0][1][:50], "bf16"))
+    assert e.value.status == B.KVQ_ERR_CAPACITY
+    B.kvq_quantize_append(cache, P.to_dev(chunks[0][0][:32], "bf16"), P.to_dev(chunks[0][1][:32], "bf16"))
+    kc = np.concatenate([live[0][0][50:], live[1][0], live[2][0], chunks[0][0][:32]])
+    vc = np.concatenate([live[0][1][50:], live[1][1], live[2][1], chunks[0][1][:32]])
+    P.assert_quantized_equal(cache, kc, vc)
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1, group=group, fp8_meta=fp8)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16")
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "ring, ragged eviction")
+
+
 def test_argument_errors(P):
     from paper_2605_26266_amd import binding as B, workloads as wl
     w = wl.WORKLOADS["small"]

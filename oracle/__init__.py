@@ -53,6 +53,7 @@ def _load():
     lib.kvqo_correction.argtypes = [ci, ci, dp, dp, cd, ci]
     lib.kvqo_correction.restype = cd
     lib.kvqo_attention.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, dp, dp]
+    lib.kvqo_attention_masked.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, ci, dp, dp]
     _lib = lib
     return lib
 
@@ -139,8 +140,9 @@ def correction(qv, step, sigma: float, mode: int) -> float:
 
 
 def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, correction: int = 1,
-              rotate: bool = True) -> Tuple[np.ndarray, np.ndarray]:
-    """One head.  q [m][d]; khat, vhat [ns][d]; kstep [ns][G]; kr, vr [nr][d] -> (out [m][d], P_S [m])."""
+              rotate: bool = True, causal: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+    """One head.  q [m][d]; khat, vhat [ns][d]; kstep [ns][G]; kr, vr [nr][d] -> (out [m][d], P_S [m]).
+    causal: current key j is visible to query r only if j <= r + nr - m."""
     q = _d(q)
     m, d = q.shape
     khat = _d(khat).reshape(-1, d)
@@ -153,11 +155,11 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
     sigma = 1.0 / np.sqrt(d) if sigma is None else float(sigma)
     out = np.empty((m, d), dtype=np.float64)
     mass = np.empty((m,), dtype=np.float64)
-    rc = _load().kvqo_attention(d, d // G, m, ns, nr, _p(q, ctypes.c_double), _p(khat, ctypes.c_double),
-                                _p(kstep, ctypes.c_double), _p(vhat, ctypes.c_double),
-                                _p(kr, ctypes.c_double), _p(vr, ctypes.c_double), sigma,
-                                int(correction), int(rotate), _p(out, ctypes.c_double),
-                                _p(mass, ctypes.c_double))
+    rc = _load().kvqo_attention_masked(d, d // G, m, ns, nr, _p(q, ctypes.c_double), _p(khat, ctypes.c_double),
+                                       _p(kstep, ctypes.c_double), _p(vhat, ctypes.c_double),
+                                       _p(kr, ctypes.c_double), _p(vr, ctypes.c_double), sigma,
+                                       int(correction), int(rotate), int(causal), _p(out, ctypes.c_double),
+                                       _p(mass, ctypes.c_double))
     if rc:
         raise ValueError("attention: bad arguments")
     return out, mass
@@ -165,23 +167,30 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
 
 def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
                     sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True,
-                    fp8_meta: bool = False):
+                    fp8_meta: bool = False, causal: bool = False):
     """Whole path for [token][head][d] inputs: quantize the cached K/V per head, then attention.
 
-    Returns (out [m][heads][d], P_S [heads][m], quantized) where quantized holds the
-    per-head codes / scales / zeros of K and V for parity checks.
+    q may have a multiple of the K/V head count (grouped-query attention): query head h uses
+    key/value head h // (q_heads // kv_heads).
+    Returns (out [m][q_heads][d], P_S [q_heads][m], quantized) where quantized holds the
+    per-KV-head codes / scales / zeros of K and V for parity checks.
     """
     q = np.asarray(q)
     m, heads, d = q.shape
+    kv_heads = np.asarray(k_cached).shape[1] if np.asarray(k_cached).shape[0] else np.asarray(k_cur).shape[1]
+    assert heads % kv_heads == 0
+    ratio = heads // kv_heads
     out = np.empty((m, heads, d), dtype=np.float64)
     mass = np.empty((heads, m), dtype=np.float64)
     quantized = []
-    for h in range(heads):
-        kc, ks, kz = quantize(np.asarray(k_cached)[:, h, :], bits, group, rotate, fp8_meta)
-        vc, vs, vz = quantize(np.asarray(v_cached)[:, h, :], bits, group, rotate, fp8_meta)
-        o, p = attention(q[:, h, :], dequantize(kc, ks, kz), ks, dequantize(vc, vs, vz),
-                         np.asarray(k_cur)[:, h, :], np.asarray(v_cur)[:, h, :], sigma, correction, rotate)
-        out[:, h, :] = o
-        mass[h] = p
+    for g in range(kv_heads):
+        kc, ks, kz = quantize(np.asarray(k_cached)[:, g, :], bits, group, rotate, fp8_meta)
+        vc, vs, vz = quantize(np.asarray(v_cached)[:, g, :], bits, group, rotate, fp8_meta)
+        khat, vhat = dequantize(kc, ks, kz), dequantize(vc, vs, vz)
+        for h in range(g * ratio, (g + 1) * ratio):
+            o, p = attention(q[:, h, :], khat, ks, vhat, np.asarray(k_cur)[:, g, :], np.asarray(v_cur)[:, g, :],
+                             sigma, correction, rotate, causal)
+            out[:, h, :] = o
+            mass[h] = p
         quantized.append(dict(k_codes=kc, k_scale=ks, k_zero=kz, v_codes=vc, v_scale=vs, v_zero=vz))
     return out, mass, quantized

@@ -337,17 +337,38 @@ double kvqo_correction(int d, int group, const double *qv, const double *step,
  * [nr][d] and queries q [m][d] are in the original basis, as is out [m][d].
  * mass_cached [m] (nullable) receives P_S.  ns == 0 or nr == 0 are allowed,
  * not both.
+ * causal != 0 (the partial-prefill setting of the cross-domain experiment: the
+ * current block is the last nr positions of a causal sequence and the queries
+ * are its last m positions): current key j is visible to query r only if
+ * j <= r + nr - m; cached keys are always visible.
  */
+int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
+                          const double *q, const double *khat, const double *kstep,
+                          const double *vhat, const double *kr, const double *vr,
+                          double sigma, int correction, int rotate, int causal,
+                          double *out, double *mass_cached);
+
 int kvqo_attention(int d, int group, int64_t m, int64_t ns, int64_t nr,
                    const double *q, const double *khat, const double *kstep,
                    const double *vhat, const double *kr, const double *vr,
                    double sigma, int correction, int rotate,
                    double *out, double *mass_cached)
 {
+    return kvqo_attention_masked(d, group, m, ns, nr, q, khat, kstep, vhat, kr, vr, sigma, correction, rotate, 0,
+                                 out, mass_cached);
+}
+
+int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
+                          const double *q, const double *khat, const double *kstep,
+                          const double *vhat, const double *kr, const double *vr,
+                          double sigma, int correction, int rotate, int causal,
+                          double *out, double *mass_cached)
+{
     if (d <= 0 || group <= 0 || d % group != 0 || m < 0 || ns < 0 || nr < 0) return 1;
     if (ns + nr == 0) return 1;
     if (rotate && !is_pow2(d)) return 1;
     if (correction < 0 || correction > 2) return 1;
+    if (causal && ns == 0 && nr < m) return 1;   /* some query would see no key at all */
     const int G = d / group;
     const double norm = inv_sqrt_d(d);
     int failed = 0;
@@ -369,16 +390,26 @@ int kvqo_attention(int d, int group, int64_t m, int64_t ns, int64_t nr,
             for (int c = 0; c < d; ++c) dot += qv[c] * khat[i * d + c];
             s[i] = sigma * dot - kvqo_correction(d, group, qv, kstep + i * G, sigma, correction);
         }
+        /* number of current keys this query sees */
+        int64_t nvis = nr;
+        if (causal) {
+            nvis = r + nr - m + 1;
+            if (nvis < 0) nvis = 0;
+            if (nvis > nr) nvis = nr;
+        }
         for (int64_t j = 0; j < nr; ++j) {
             double dot = 0.0;
             for (int c = 0; c < d; ++c) dot += qr[c] * kr[j * d + c];
             s[ns + j] = sigma * dot;
         }
-        double top = s[0];
-        for (int64_t i = 1; i < ns + nr; ++i) if (s[i] > top) top = s[i];
+        double top = ns > 0 ? s[0] : s[ns];
+        for (int64_t i = 0; i < ns + nvis; ++i) if (s[i] > top) top = s[i];
         double zs = 0.0, zr = 0.0;
         for (int64_t i = 0; i < ns; ++i) { s[i] = exp(s[i] - top); zs += s[i]; }
-        for (int64_t j = ns; j < ns + nr; ++j) { s[j] = exp(s[j] - top); zr += s[j]; }
+        for (int64_t j = ns; j < ns + nr; ++j) {
+            s[j] = j < ns + nvis ? exp(s[j] - top) : 0.0;   /* masked keys get weight 0 */
+            zr += s[j];
+        }
         const double z = zs + zr;
         for (int c = 0; c < d; ++c) acc[c] = 0.0;
         for (int64_t i = 0; i < ns; ++i) {

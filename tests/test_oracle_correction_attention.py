@@ -277,3 +277,42 @@ def test_whole_path_direction_on_the_tiny_config(oracle):
     steal2, steal4 = np.mean(raw2[0] - clean), np.mean(raw4[0] - clean)
     assert steal2 > 0 and steal2 > 3 * abs(steal4)
     assert abs(np.mean(fix2[0] - clean)) < steal2
+
+
+def test_causal_mask_against_textbook_masked_softmax(oracle):
+    """The causal option against an independent numpy statement of masked softmax attention (no
+    quantization error: step 0), with and without a cached prefix, m == nr and m < nr."""
+    rng = np.random.default_rng(21)
+    d = 16
+    for (m, ns, nr) in ((7, 5, 7), (4, 0, 9), (6, 3, 10)):
+        q, kr, vr = rng.standard_normal((m, d)), rng.standard_normal((nr, d)), rng.standard_normal((nr, d))
+        ks, vs = rng.standard_normal((ns, d)), rng.standard_normal((ns, d))
+        out, mass = oracle.attention(q, ks, np.zeros((ns, 1)), vs, kr, vr, correction=1, rotate=False, causal=True)
+        s = np.concatenate([q @ ks.T, q @ kr.T], axis=1) / np.sqrt(d)
+        vis = np.ones((m, ns + nr), dtype=bool)
+        for r in range(m):
+            vis[r, ns + r + nr - m + 1:] = False
+        s = np.where(vis, s, -np.inf)
+        p = np.exp(s - s.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        want = p @ np.concatenate([vs, vr])
+        assert np.allclose(out, want, rtol=1e-12, atol=1e-12)
+        assert np.allclose(mass, p[:, :ns].sum(axis=1), rtol=1e-12, atol=1e-14)
+    # the last query row sees every key: identical to the unmasked call
+    full, _ = oracle.attention(q, ks, np.zeros((ns, 1)), vs, kr, vr, correction=1, rotate=False)
+    assert np.allclose(out[-1], full[-1], rtol=1e-13)
+
+
+def test_grouped_query_heads_share_the_cache(oracle):
+    rng = np.random.default_rng(4)
+    from paper_2605_26266_amd import workloads as wl
+    d, m, ns, nr = 64, 5, 40, 6
+    q = wl.round_to_bf16(rng.standard_normal((m, 6, d)).astype(np.float32))
+    kc, vc = (wl.round_to_bf16(rng.standard_normal((ns, 2, d)).astype(np.float32)) for _ in range(2))
+    kr, vr = (wl.round_to_bf16(rng.standard_normal((nr, 2, d)).astype(np.float32)) for _ in range(2))
+    out, mass, quant = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1)
+    assert len(quant) == 2 and out.shape == (m, 6, d) and mass.shape == (6, m)
+    for h in range(6):
+        o1, m1, _ = oracle.chunk_attention(q[:, h:h + 1], kc[:, h // 3:h // 3 + 1], vc[:, h // 3:h // 3 + 1],
+                                           kr[:, h // 3:h // 3 + 1], vr[:, h // 3:h // 3 + 1], 2, 1)
+        assert np.array_equal(o1[:, 0], out[:, h]) and np.array_equal(m1[0], mass[h])

@@ -149,6 +149,30 @@ kvq_status kvq_chunk_attention(const kvq_cache *cache, int64_t cache_start, int6
                                float softmax_scale, int correction,
                                void *out, float *mass_cached, void *hip_stream);
 
+/*
+ * kvq_chunk_attention with the options of the partial-prefill setting (the paper's cross-domain
+ * experiment: a quantized cached prefix and a multi-token causal current block in one softmax).
+ *   q_heads_per_kv_head  grouped-query attention: q, out and mass_cached have num_heads * this heads;
+ *                        query head h attends to key/value head h / this.  1 = as kvq_chunk_attention.
+ *   causal               1: current key j is visible to query row r only if j <= r + n_cur - m (the
+ *                        queries are the last m positions of the current block; requires n_cur >= m).
+ *                        Cached keys are always visible.
+ *   q_stride_token/head  element strides of q and out (stride_token / stride_head of the call are those
+ *                        of k_cur and v_cur); 0, 0 = the same strides.
+ * opts == NULL is kvq_chunk_attention.  mass_cached: [num_heads * q_heads_per_kv_head][m].
+ */
+typedef struct {
+    int32_t q_heads_per_kv_head;
+    int32_t causal;
+    int64_t q_stride_token, q_stride_head;
+} kvq_attention_opts;
+
+kvq_status kvq_chunk_attention_ex(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                  const void *q, const void *k_cur, const void *v_cur,
+                                  int64_t m, int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                  float softmax_scale, int correction, const kvq_attention_opts *opts,
+                                  void *out, float *mass_cached, void *hip_stream);
+
 /* Same contract as kvq_chunk_attention, but always runs the fp32 vector-ALU kernel (Alg. 1 in
  * single precision, no matrix cores): slow, for reference-precision results on any cache. */
 kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,

@@ -22,6 +22,7 @@ KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
 EXPORTED = (
     "kvq_cache_bytes", "kvq_cache_create", "kvq_cache_destroy", "kvq_cache_len", "kvq_cache_reset",
     "kvq_cache_truncate", "kvq_cache_evict", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
+    "kvq_chunk_attention_ex",
     "kvq_cache_export", "kvq_status_string", "kvq_version",
 )
 
@@ -30,6 +31,11 @@ class kvq_cache_desc(ctypes.Structure):
     _fields_ = [("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("bits", ctypes.c_int32),
                 ("group_size", ctypes.c_int32), ("rotate", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
                 ("meta_format", ctypes.c_int32), ("capacity_tokens", ctypes.c_int64)]
+
+
+class kvq_attention_opts(ctypes.Structure):
+    _fields_ = [("q_heads_per_kv_head", ctypes.c_int32), ("causal", ctypes.c_int32),
+                ("q_stride_token", ctypes.c_int64), ("q_stride_head", ctypes.c_int64)]
 
 
 class KvqError(RuntimeError):
@@ -65,6 +71,7 @@ def lib() -> ctypes.CDLL:
     att = [vp, i64, i64, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp, vp, vp]
     L.kvq_chunk_attention.argtypes = att
     L.kvq_chunk_attention_fp32.argtypes = att
+    L.kvq_chunk_attention_ex.argtypes = att[:12] + [ctypes.POINTER(kvq_attention_opts)] + att[12:]
     L.kvq_cache_export.argtypes = [vp, ci, i64, i64, vp, vp, vp, vp]
     L.kvq_status_string.argtypes = [ci]
     L.kvq_status_string.restype = ctypes.c_char_p
@@ -196,6 +203,32 @@ def kvq_chunk_attention(cache: Cache, cache_start: int, cache_len: int, q: torch
                         correction: int = 1, stream: Optional[torch.cuda.Stream] = None) -> None:
     _attention(lib().kvq_chunk_attention, cache, cache_start, cache_len, q, k_cur, v_cur, softmax_scale, correction,
                out, mass_cached, stream)
+
+
+def kvq_chunk_attention_ex(cache: Cache, cache_start: int, cache_len: int, q: torch.Tensor,
+                           k_cur: Optional[torch.Tensor], v_cur: Optional[torch.Tensor], out: torch.Tensor,
+                           mass_cached: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                           correction: int = 1, causal: bool = False,
+                           stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Grouped-query heads (q has a multiple of the cache's head count) and / or a causal current block."""
+    kv = k_cur if k_cur is not None else v_cur
+    if q.shape[1] % cache.desc.num_heads != 0:
+        raise ValueError("query heads must be a multiple of the cache's heads")
+    for t in (k_cur, v_cur):
+        if t is not None and (t.dtype != cache.torch_dtype or (kv.shape[0] > 0 and _tok_head_strides(t) != _tok_head_strides(kv))):
+            raise ValueError("k_cur and v_cur must share dtype and strides")
+    if q.dtype != cache.torch_dtype or out.dtype != cache.torch_dtype or _tok_head_strides(out) != _tok_head_strides(q):
+        raise ValueError("q and out must be in the cache's io dtype and share strides")
+    if mass_cached is not None and (mass_cached.dtype != torch.float32 or not mass_cached.is_contiguous()):
+        raise ValueError("mass_cached must be a contiguous float32 [query heads][m] tensor")
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(kv) if kv is not None and kv.shape[0] > 0 else (cache.desc.num_heads * cache.desc.head_dim, cache.desc.head_dim)
+    opts = kvq_attention_opts(q.shape[1] // cache.desc.num_heads, int(bool(causal)), qst, qsh)
+    n_cur = 0 if k_cur is None else k_cur.shape[0]
+    _check(lib().kvq_chunk_attention_ex(cache.handle, int(cache_start), int(cache_len), q.data_ptr(), _ptr(k_cur),
+                                        _ptr(v_cur), q.shape[0], n_cur, st, sh, float(softmax_scale), int(correction),
+                                        ctypes.byref(opts), out.data_ptr(), _ptr(mass_cached), _stream(stream)),
+           "kvq_chunk_attention_ex")
 
 
 def kvq_chunk_attention_fp32(cache: Cache, cache_start: int, cache_len: int, q: torch.Tensor,

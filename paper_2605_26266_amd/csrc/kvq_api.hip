@@ -158,8 +158,19 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
                                    const void *q, const void *k_cur, const void *v_cur, int64_t m,
                                    int64_t n_cur, int64_t stride_token, int64_t stride_head,
                                    float softmax_scale, int correction, void *out, float *mass_cached,
-                                   void *hip_stream, bool force_vector)
+                                   void *hip_stream, bool force_vector, const kvq_attention_opts *opts = nullptr)
 {
+    kvq_attention_opts o = {1, 0, stride_token, stride_head};
+    if (opts) {
+        o = *opts;
+        if (o.q_stride_token == 0 && o.q_stride_head == 0) {
+            o.q_stride_token = stride_token;
+            o.q_stride_head = stride_head;
+        }
+        if (o.q_heads_per_kv_head < 1 || o.q_heads_per_kv_head > 64) return KVQ_ERR_INVALID_ARG;
+        if (o.causal != 0 && o.causal != 1) return KVQ_ERR_INVALID_ARG;
+        if (o.causal && n_cur < m) return KVQ_ERR_INVALID_ARG;   // the queries are the last m current positions
+    }
     if (!cache || m < 0 || n_cur < 0 || cache_len < 0 || cache_start < 0) return KVQ_ERR_INVALID_ARG;
     if (cache_start + cache_len > cache->len) return KVQ_ERR_INVALID_ARG;
     if (cache_len == 0 && n_cur == 0) return KVQ_ERR_INVALID_ARG;
@@ -167,8 +178,8 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     if (!(softmax_scale >= 0.0f) || !(softmax_scale < 3.0e38f)) return KVQ_ERR_INVALID_ARG;
     if (m == 0) return KVQ_OK;
     const kvq_cache_desc &d = cache->desc;
-    if (!tensor_ok(q, stride_token, stride_head, d.head_dim, d.io_dtype) ||
-        !tensor_ok(out, stride_token, stride_head, d.head_dim, d.io_dtype))
+    if (!tensor_ok(q, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype) ||
+        !tensor_ok(out, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype))
         return KVQ_ERR_INVALID_ARG;
     if (n_cur > 0 && (!tensor_ok(k_cur, stride_token, stride_head, d.head_dim, d.io_dtype) ||
                       !tensor_ok(v_cur, stride_token, stride_head, d.head_dim, d.io_dtype)))
@@ -189,6 +200,10 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.n_cur = n_cur;
     a.stride_token = stride_token;
     a.stride_head = stride_head;
+    a.q_stride_token = o.q_stride_token;
+    a.q_stride_head = o.q_stride_head;
+    a.q_per_kv = o.q_heads_per_kv_head;
+    a.causal = o.causal;
     a.softmax_scale = softmax_scale > 0.0f ? softmax_scale : (d.head_dim == 64 ? 0.125f : 0.088388347648318f);
     a.correction = correction;
     a.out = out;
@@ -223,6 +238,16 @@ kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start,
 {
     return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
                             softmax_scale, correction, out, mass_cached, hip_stream, true);
+}
+
+kvq_status kvq_chunk_attention_ex(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                  const void *q, const void *k_cur, const void *v_cur, int64_t m,
+                                  int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                  float softmax_scale, int correction, const kvq_attention_opts *opts,
+                                  void *out, float *mass_cached, void *hip_stream)
+{
+    return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
+                            softmax_scale, correction, out, mass_cached, hip_stream, false, opts);
 }
 
 kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count, uint8_t *codes,

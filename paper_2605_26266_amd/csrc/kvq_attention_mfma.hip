@@ -90,23 +90,29 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int n = lane & 31, hh = lane >> 5;
 
-    // Workgroups are handed to the 8 XCDs round-robin; keep all row blocks of a head on one XCD so
-    // that its packed cache is fetched into that XCD's L2 once.
-    int head, rblk;
+    // Workgroups are handed to the 8 XCDs round-robin; keep all row blocks of all query heads of a
+    // key/value head on one XCD so that its packed cache is fetched into that XCD's L2 once.
+    int head, qhead, rblk;   // key/value head, query head, 256-row block
     {
         const int bid = blockIdx.x;
+        const int per_head = row_blocks * a.q_per_kv;
+        int j;
         if ((cv.num_heads & 7) == 0) {
-            const int xcd = bid & 7, j = bid >> 3;
-            head = (j / row_blocks) * 8 + xcd;
-            rblk = j % row_blocks;
+            const int xcd = bid & 7;
+            j = bid >> 3;
+            head = (j / per_head) * 8 + xcd;
         } else {
-            head = bid / row_blocks;
-            rblk = bid % row_blocks;
+            j = bid;
+            head = j / per_head;
         }
+        const int local = j % per_head;
+        qhead = head * a.q_per_kv + local / row_blocks;
+        rblk = local % row_blocks;
     }
     const int64_t wave_row0 = (int64_t)rblk * kRowsPerBlock + wave * kRowsPerWave;
-    const int64_t head_off = (int64_t)head * a.stride_head;
-    const uint16_t *q_base = static_cast<const uint16_t *>(a.q) + head_off;
+    const int64_t head_off = (int64_t)head * a.stride_head;          // k_cur / v_cur
+    const int64_t qhead_off = (int64_t)qhead * a.q_stride_head;      // q / out
+    const uint16_t *q_base = static_cast<const uint16_t *>(a.q) + qhead_off;
     const float c_log = a.softmax_scale * kLog2e;
     const UnpackConsts uc = make_unpack_consts<BITS>();
 
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const int prow = tid / kPrepLanes, ppart = tid % kPrepLanes;
         int64_t row = (int64_t)rblk * kRowsPerBlock + prow;
         row = row < a.m ? row : a.m - 1;
-        const uint4 *src = reinterpret_cast<const uint4 *>(q_base + row * a.stride_token + ppart * kPrepCh);
+        const uint4 *src = reinterpret_cast<const uint4 *>(q_base + row * a.q_stride_token + ppart * kPrepCh);
         float x[kPrepCh];
 #pragma unroll
         for (int i = 0; i < kPrepCh / 8; ++i) {
@@ -764,14 +770,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         for (int rb = 0; rb < kRB; ++rb) {
             int64_t row = wave_row0 + 32 * rb + n;
             row = row < a.m ? row : a.m - 1;
-            const uint16_t *src = q_base + row * a.stride_token + 8 * hh;
+            const uint16_t *src = q_base + row * a.q_stride_token + 8 * hh;
 #pragma unroll
             for (int s = 0; s < 8; ++s) qop[rb][s] = *reinterpret_cast<const u32x4 *>(src + 16 * s);
         }
         // V^T staging: two buffers of 128 channel rows x 32 tokens (bf16), reusing the query staging area.
         __syncthreads();
         auto vt = [&](int i) -> uint16_t * { return reinterpret_cast<uint16_t *>(q_stage + (i & 1) * D * kVtRowWords); };
-        const int n_tiles = (int)((a.n_cur + kTileTokens - 1) / kTileTokens);
+        // Under the causal mask the tiles past the last row of this workgroup are skipped by all its waves.
+        int64_t n_keys = a.n_cur;
+        if (a.causal) {
+            int64_t last_row = (int64_t)rblk * kRowsPerBlock + kRowsPerBlock - 1;
+            last_row = last_row < a.m ? last_row : a.m - 1;
+            const int64_t upto = last_row + (a.n_cur - a.m) + 1;
+            n_keys = upto < n_keys ? upto : n_keys;
+        }
+        const int n_tiles = (int)((n_keys + kTileTokens - 1) / kTileTokens);
         constexpr int kVtIters = 16 * 32 / kThreads;     // 16 channel octets x 32 tokens per tile
         constexpr int kVtOcts = kThreads / 32;
         u32x4 pre_vt[kVtIters];
@@ -813,16 +827,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 for (int rb = 0; rb < kRB; ++rb) s[rb] = mfma_bf16(kop[slab], qop[rb][slab], s[rb]);
             }
             const int64_t key_base = (int64_t)tile * kTileTokens + 4 * hh;
-            const bool edge = (int64_t)(tile + 1) * kTileTokens > a.n_cur;
+            const bool edge = a.causal != 0 || (int64_t)(tile + 1) * kTileTokens > a.n_cur;
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(s[rb][v], c_log, -m_ref[rb]);
                 if (edge) {
+                    // keys this row sees: all of them, or under the causal mask those up to its own position
+                    int64_t visible = a.n_cur;
+                    if (a.causal) {
+                        const int64_t upto = wave_row0 + 32 * rb + n + (a.n_cur - a.m) + 1;
+                        visible = upto < visible ? upto : visible;
+                    }
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int64_t kk = key_base + 8 * (v >> 2) + (v & 3);
-                        e[rb][v] = kk < a.n_cur ? e[rb][v] : kMaskBias;
+                        e[rb][v] = kk < visible ? e[rb][v] : kMaskBias;
                     }
                 }
                 float mx = fmaxf(e[rb][0], e[rb][1]);
@@ -889,7 +909,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     }
 
     // ------------------------------------------------------------------------- epilogue ----
-    uint16_t *out_base = static_cast<uint16_t *>(a.out) + head_off;
+    uint16_t *out_base = static_cast<uint16_t *>(a.out) + qhead_off;
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
         const float ls = l_s[rb] + xhalf(l_s[rb]);
@@ -897,7 +917,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const float inv = 1.0f / (ls + lr);
         const int64_t row = wave_row0 + 32 * rb + n;
         if (row < a.m) {
-            uint16_t *dst = out_base + row * a.stride_token + 4 * hh;
+            uint16_t *dst = out_base + row * a.q_stride_token + 4 * hh;
 #pragma unroll
             for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -907,7 +927,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     w.y = pack_bf16(o[b][rb][4 * g + 2] * inv, o[b][rb][4 * g + 3] * inv);
                     *reinterpret_cast<u32x2 *>(dst + 32 * b + 8 * g) = w;
                 }
-            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)head * a.m + row] = ls * inv;
+            if (a.mass_cached && hh == 0) a.mass_cached[(int64_t)qhead * a.m + row] = ls * inv;
         }
     }
 }
@@ -922,7 +942,7 @@ template <int BITS, bool CORR, bool FP8META> hipError_t launch(const AttentionAr
         configured = true;
     }
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
-    const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads;
+    const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR, FP8META>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
                        a, row_blocks);

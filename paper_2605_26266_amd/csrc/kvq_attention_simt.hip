@@ -68,13 +68,21 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     __shared__ float corr_g[4];  // softmax_scale^2 / 24 * nu_j per group (at most 4 groups)
     const CacheView &cv = a.cv;
     const int c = threadIdx.x;
-    const int head = blockIdx.y;
+    const int qhead = blockIdx.y;               // query head
+    const int head = qhead / a.q_per_kv;        // key/value head
     const int64_t row = blockIdx.x;
+    // current keys this row sees (all of them, or under the causal mask those up to its own position)
+    int64_t n_vis = a.n_cur;
+    if (a.causal) {
+        const int64_t upto = row + (a.n_cur - a.m) + 1;
+        n_vis = upto < n_vis ? upto : n_vis;
+        n_vis = n_vis < 0 ? 0 : n_vis;
+    }
     const float norm = D == 64 ? 0.125f : 0.088388347648318f;
     const float sigma = a.softmax_scale;
     const float off = code_offset(BITS);
 
-    const T *qp = static_cast<const T *>(a.q) + row * a.stride_token + (int64_t)head * a.stride_head;
+    const T *qp = static_cast<const T *>(a.q) + row * a.q_stride_token + (int64_t)qhead * a.q_stride_head;
     const float qc = Io<T>::load(qp + c);
     q_raw[c] = qc;
     q_rot[c] = qc;
@@ -147,7 +155,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     // Pass 1: row maximum.
     float mx = -INFINITY;
     for (int64_t i = c; i < a.cache_len; i += D) mx = fmaxf(mx, cached_score(a.cache_start + i));
-    for (int64_t j = c; j < a.n_cur; j += D) mx = fmaxf(mx, current_score(j));
+    for (int64_t j = c; j < n_vis; j += D) mx = fmaxf(mx, current_score(j));
     mx = block_reduce<D>(mx, scratch, c, true);
 
     // Pass 2: weights and weighted sums.
@@ -184,14 +192,14 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     fwht_lds<D>(scratch, c);
     acc = scratch[c] * norm;
     __syncthreads();
-    for (int64_t base = 0; base < a.n_cur; base += D) {
+    for (int64_t base = 0; base < n_vis; base += D) {
         const int64_t j = base + c;
-        const float p = j < a.n_cur ? expf(current_score(j) - mx) : 0.0f;
+        const float p = j < n_vis ? expf(current_score(j) - mx) : 0.0f;
         sum_r += p;
         __syncthreads();
         p_blk[c] = p;
         __syncthreads();
-        const int cnt = (int)((a.n_cur - base) < D ? (a.n_cur - base) : D);
+        const int cnt = (int)((n_vis - base) < D ? (n_vis - base) : D);
         for (int jj = 0; jj < cnt; ++jj) {
             const T *vp = static_cast<const T *>(a.v_cur) + (base + jj) * a.stride_token + (int64_t)head * a.stride_head;
             acc = fmaf(p_blk[jj], Io<T>::load(vp + c), acc);
@@ -200,16 +208,16 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     sum_s = block_reduce<D>(sum_s, scratch, c, false);
     sum_r = block_reduce<D>(sum_r, scratch, c, false);
     const float inv = 1.0f / (sum_s + sum_r);
-    T *op = static_cast<T *>(a.out) + row * a.stride_token + (int64_t)head * a.stride_head;
+    T *op = static_cast<T *>(a.out) + row * a.q_stride_token + (int64_t)qhead * a.q_stride_head;
     Io<T>::store(op + c, acc * inv);
-    if (a.mass_cached && c == 0) a.mass_cached[(int64_t)head * a.m + row] = sum_s * inv;
+    if (a.mass_cached && c == 0) a.mass_cached[(int64_t)qhead * a.m + row] = sum_s * inv;
 }
 
 }  // namespace
 
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream)
 {
-    const dim3 grid((unsigned)a.m, (unsigned)a.cv.num_heads);
+    const dim3 grid((unsigned)a.m, (unsigned)(a.cv.num_heads * a.q_per_kv));
     const bool bf16 = a.cv.io_dtype == KVQ_BF16;
 #define KVQ_A(D, B)                                                                                         \
     if (a.cv.head_dim == D && a.cv.bits == B) {                                                             \

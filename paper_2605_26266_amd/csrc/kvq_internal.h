@@ -117,7 +117,10 @@ struct AttentionArgs {
     int64_t cache_start, cache_len;   // logical token positions (the storage is a ring of cap_tiles tiles)
     int64_t phys_tile_first;          // physical tile that holds logical token cache_start
     const void *q, *k_cur, *v_cur;
-    int64_t m, n_cur, stride_token, stride_head;
+    int64_t m, n_cur, stride_token, stride_head;   // strides of k_cur / v_cur
+    int64_t q_stride_token, q_stride_head;         // strides of q / out
+    int32_t q_per_kv;   // query heads per key/value head (grouped-query attention); query head h uses KV head h / q_per_kv
+    int32_t causal;     // current key j visible to query row r only if j <= r + n_cur - m
     float softmax_scale;
     int correction;
     void *out;

@@ -63,26 +63,36 @@ def assert_quantized_equal(cache: B.Cache, k: np.ndarray, v: np.ndarray, heads=N
 
 
 def run_gpu_attention(cache, q, k_cur, v_cur, io_dtype, cache_start=0, cache_len=None, correction=1,
-                      softmax_scale=0.0, fp32_kernel=False):
-    """q/k_cur/v_cur: float32 numpy [tokens][H][d].  Returns (out float64 [m][H][d], mass float64 [H][m])."""
+                      softmax_scale=0.0, fp32_kernel=False, causal=None):
+    """q/k_cur/v_cur: float32 numpy [tokens][H][d].  Returns (out float64 [m][H][d], mass float64 [H][m]).
+    causal not None: the extended entry point (grouped query heads, optional causal current block)."""
     cache_len = len(cache) - cache_start if cache_len is None else cache_len
     qd = to_dev(q, io_dtype)
     kd = to_dev(k_cur, io_dtype) if k_cur is not None and k_cur.shape[0] else None
     vd = to_dev(v_cur, io_dtype) if v_cur is not None and v_cur.shape[0] else None
     out = torch.full_like(qd, float("nan"))
     mass = torch.full((q.shape[1], q.shape[0]), float("nan"), dtype=torch.float32, device=DEV)
+    if causal is not None:
+        B.kvq_chunk_attention_ex(cache, cache_start, cache_len, qd, kd, vd, out, mass, softmax_scale, correction,
+                                 causal=causal)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy().astype(np.float64), mass.cpu().numpy().astype(np.float64)
     fn = B.kvq_chunk_attention_fp32 if fp32_kernel else B.kvq_chunk_attention
     fn(cache, cache_start, cache_len, qd, kd, vd, out, mass, softmax_scale, correction)
     torch.cuda.synchronize()
     return out.float().cpu().numpy().astype(np.float64), mass.cpu().numpy().astype(np.float64)
 
 
-def assert_attention_close(out_gpu, mass_gpu, out_ref, mass_ref, tol_out, what=""):
+def assert_attention_close(out_gpu, mass_gpu, out_ref, mass_ref, tol_out, what="", mass_floor=None):
+    """mass_floor: smallest probability the relative bar is applied to (default MASS_FLOOR).  P_R is
+    derived from the fp32 P_S that the call returns, which resolves 6e-8 near 1: rows that see one or two
+    current keys under a causal mask need a higher floor for the bar to measure the kernel, not the format."""
+    mass_floor = MASS_FLOOR if mass_floor is None else mass_floor
     assert np.all(np.isfinite(out_gpu)), what + ": non-finite output"
     err = float(np.max(np.abs(out_gpu - out_ref)))
     assert err <= tol_out, "%s: max |O - O_oracle| = %.3e > %.1e" % (what, err, tol_out)
     for got, ref, name in ((mass_gpu, mass_ref, "P_S"), (1.0 - mass_gpu, 1.0 - mass_ref, "P_R")):
-        sel = ref >= MASS_FLOOR
+        sel = ref >= mass_floor
         if np.any(sel):
             rel = float(np.max(np.abs(got[sel] - ref[sel]) / ref[sel]))
             assert rel <= TOL_MASS_REL, "%s: %s relative error %.3e > %.0e" % (what, name, rel, TOL_MASS_REL)

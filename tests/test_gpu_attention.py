@@ -317,6 +317,38 @@ def test_sliding_window_ring(P, group, fp8):
     P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "ring, ragged eviction")
 
 
+@pytest.mark.parametrize("io,group,fp8", [("bf16", None, False), ("bf16", 32, True), ("fp32", None, False)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_grouped_query_heads_and_causal_block(P, io, group, fp8, causal):
+    """Partial-prefill shape: 6 query heads over 2 key/value heads, the current block causal.  Runs the
+    per-token and the group-wise matrix-core kernels (bf16) and the vector kernel (fp32 I/O)."""
+    import oracle
+    from dataclasses import replace
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = replace(wl.WORKLOADS["small"], io_dtype=io)
+    kv_heads, ratio, n_cached = 2, 3, 500
+    cache = P.make_cache(w, n_cached, heads=kv_heads, group=group, fp8_meta=fp8)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(kv_heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(kc, io), P.to_dev(vc, io))
+    q_all = wl.chunk_q(w, heads=range(kv_heads * ratio))
+    tol = P.TOL_OUT_BF16 if io == "bf16" else P.TOL_OUT_FP32
+    for (m, n_cur) in ((300, 300), (70, 333), (1, 64)):      # several row blocks; queries = tail of the block; one query
+        kr, vr = wl.chunk_kv(w, 1, heads=range(kv_heads), n_tokens=n_cur)
+        q = q_all[:m]
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1, group=group, fp8_meta=fp8, causal=causal)
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, io, causal=causal)
+        P.assert_attention_close(out, mass, ref, mass_ref, tol, "gqa causal=%s m=%d n=%d" % (causal, m, n_cur),
+                                 mass_floor=1e-4 if causal else None)
+    # no cached keys at all: pure causal self-attention of the block
+    kr, vr = wl.chunk_kv(w, 1, heads=range(kv_heads), n_tokens=96)
+    q = q_all[:96]
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc[:0], vc[:0], kr, vr, 2, 1, group=group, fp8_meta=fp8, causal=causal)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, io, cache_len=0, causal=causal)
+    P.assert_attention_close(out, mass, ref, mass_ref, tol, "gqa no cache", mass_floor=1e-4 if causal else None)
+    with pytest.raises(B.KvqError):      # causal needs the queries to be the tail of the current block
+        P.run_gpu_attention(cache, q_all[:100], kr, vr, io, causal=True)
+
+
 def test_argument_errors(P):
     from paper_2605_26266_amd import binding as B, workloads as wl
     w = wl.WORKLOADS["small"]

@@ -53,7 +53,7 @@ def _load():
     lib.kvqo_correction.argtypes = [ci, ci, dp, dp, cd, ci]
     lib.kvqo_correction.restype = cd
     lib.kvqo_attention.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, dp, dp]
-    lib.kvqo_attention_masked.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, ci, dp, dp]
+    lib.kvqo_attention_masked.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, cd, ci, ci, ci, dp, dp, dp]
     _lib = lib
     return lib
 
@@ -79,12 +79,24 @@ def hadamard(x) -> np.ndarray:
     return u
 
 
-def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True, fp8_meta: bool = False
-             ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def _signs(signs, d: int) -> Optional[np.ndarray]:
+    if signs is None:
+        return None
+    s = _d(signs).reshape(d)
+    if not np.all(np.abs(s) == 1.0):
+        raise ValueError("signs must be +1 / -1")
+    return s
+
+
+def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True, fp8_meta: bool = False,
+             signs=None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """x [rows][d] -> codes uint8 [rows][d], scale float32 [rows][G], zero float32 [rows][G].
 
-    fp8_meta: the stored scale is an FP8 E4M3 value and the stored zero-point a BF16 value."""
+    fp8_meta: the stored scale is an FP8 E4M3 value and the stored zero-point a BF16 value.
+    signs [d] of +1/-1 (with rotate): randomised Hadamard rotation, x -> Hn (signs * x)."""
     x = _d(x)
+    if signs is not None and rotate:
+        x = np.ascontiguousarray(x * _signs(signs, x.shape[1])[None, :])   # exact: entries are +-1
     rows, d = x.shape
     group = d if group is None else group
     codes = np.empty((rows, d), dtype=np.uint8)
@@ -140,9 +152,10 @@ def correction(qv, step, sigma: float, mode: int) -> float:
 
 
 def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, correction: int = 1,
-              rotate: bool = True, causal: bool = False) -> Tuple[np.ndarray, np.ndarray]:
+              rotate: bool = True, causal: bool = False, signs=None) -> Tuple[np.ndarray, np.ndarray]:
     """One head.  q [m][d]; khat, vhat [ns][d]; kstep [ns][G]; kr, vr [nr][d] -> (out [m][d], P_S [m]).
-    causal: current key j is visible to query r only if j <= r + nr - m."""
+    causal: current key j is visible to query r only if j <= r + nr - m.
+    signs [d] of +1/-1: the cache basis is the randomised rotation x -> Hn (signs * x)."""
     q = _d(q)
     m, d = q.shape
     khat = _d(khat).reshape(-1, d)
@@ -155,10 +168,12 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
     sigma = 1.0 / np.sqrt(d) if sigma is None else float(sigma)
     out = np.empty((m, d), dtype=np.float64)
     mass = np.empty((m,), dtype=np.float64)
+    sg = _signs(signs, d) if rotate else None
     rc = _load().kvqo_attention_masked(d, d // G, m, ns, nr, _p(q, ctypes.c_double), _p(khat, ctypes.c_double),
                                        _p(kstep, ctypes.c_double), _p(vhat, ctypes.c_double),
                                        _p(kr, ctypes.c_double), _p(vr, ctypes.c_double), sigma,
-                                       int(correction), int(rotate), int(causal), _p(out, ctypes.c_double),
+                                       int(correction), int(rotate), int(causal),
+                                       None if sg is None else _p(sg, ctypes.c_double), _p(out, ctypes.c_double),
                                        _p(mass, ctypes.c_double))
     if rc:
         raise ValueError("attention: bad arguments")
@@ -167,7 +182,7 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
 
 def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
                     sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True,
-                    fp8_meta: bool = False, causal: bool = False):
+                    fp8_meta: bool = False, causal: bool = False, signs=None):
     """Whole path for [token][head][d] inputs: quantize the cached K/V per head, then attention.
 
     q may have a multiple of the K/V head count (grouped-query attention): query head h uses
@@ -184,12 +199,12 @@ def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: 
     mass = np.empty((heads, m), dtype=np.float64)
     quantized = []
     for g in range(kv_heads):
-        kc, ks, kz = quantize(np.asarray(k_cached)[:, g, :], bits, group, rotate, fp8_meta)
-        vc, vs, vz = quantize(np.asarray(v_cached)[:, g, :], bits, group, rotate, fp8_meta)
+        kc, ks, kz = quantize(np.asarray(k_cached)[:, g, :], bits, group, rotate, fp8_meta, signs)
+        vc, vs, vz = quantize(np.asarray(v_cached)[:, g, :], bits, group, rotate, fp8_meta, signs)
         khat, vhat = dequantize(kc, ks, kz), dequantize(vc, vs, vz)
         for h in range(g * ratio, (g + 1) * ratio):
             o, p = attention(q[:, h, :], khat, ks, vhat, np.asarray(k_cur)[:, g, :], np.asarray(v_cur)[:, g, :],
-                             sigma, correction, rotate, causal)
+                             sigma, correction, rotate, causal, signs)
             out[:, h, :] = o
             mass[h] = p
         quantized.append(dict(k_codes=kc, k_scale=ks, k_zero=kz, v_codes=vc, v_scale=vs, v_zero=vz))

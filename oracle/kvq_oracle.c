@@ -341,11 +341,16 @@ double kvqo_correction(int d, int group, const double *qv, const double *step,
  * current block is the last nr positions of a causal sequence and the queries
  * are its last m positions): current key j is visible to query r only if
  * j <= r + nr - m; cached keys are always visible.
+ * signs (nullable, [d], entries +1 / -1; used only with rotate != 0): the
+ * randomised Hadamard rotation of the rotation paragraph of the method section,
+ * x -> Hn (signs * x).  The cache was quantized in that basis, so the query is
+ * mapped the same way and the cached part of the output is mapped back with
+ * the transpose, o_S = signs * (Hn^T acc).
  */
 int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
                           const double *q, const double *khat, const double *kstep,
                           const double *vhat, const double *kr, const double *vr,
-                          double sigma, int correction, int rotate, int causal,
+                          double sigma, int correction, int rotate, int causal, const double *signs,
                           double *out, double *mass_cached);
 
 int kvqo_attention(int d, int group, int64_t m, int64_t ns, int64_t nr,
@@ -354,14 +359,14 @@ int kvqo_attention(int d, int group, int64_t m, int64_t ns, int64_t nr,
                    double sigma, int correction, int rotate,
                    double *out, double *mass_cached)
 {
-    return kvqo_attention_masked(d, group, m, ns, nr, q, khat, kstep, vhat, kr, vr, sigma, correction, rotate, 0,
+    return kvqo_attention_masked(d, group, m, ns, nr, q, khat, kstep, vhat, kr, vr, sigma, correction, rotate, 0, NULL,
                                  out, mass_cached);
 }
 
 int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
                           const double *q, const double *khat, const double *kstep,
                           const double *vhat, const double *kr, const double *vr,
-                          double sigma, int correction, int rotate, int causal,
+                          double sigma, int correction, int rotate, int causal, const double *signs,
                           double *out, double *mass_cached)
 {
     if (d <= 0 || group <= 0 || d % group != 0 || m < 0 || ns < 0 || nr < 0) return 1;
@@ -380,7 +385,9 @@ int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
         double *acc = qv + d, *tmp = acc + d;
         const double *qr = q + r * d;
         if (rotate) {
-            kvqo_hadamard(d, qr, qv);
+            /* randomised rotation: channel signs first, then the Hadamard matrix */
+            if (signs) { for (int c = 0; c < d; ++c) tmp[c] = signs[c] * qr[c]; }
+            kvqo_hadamard(d, signs ? tmp : qr, qv);
             for (int c = 0; c < d; ++c) qv[c] *= norm;
         } else {
             memcpy(qv, qr, sizeof(double) * (size_t)d);
@@ -419,7 +426,7 @@ int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
         if (rotate) {
             /* Hn is symmetric, so Hn^T acc is the same dense product. */
             kvqo_hadamard(d, acc, tmp);
-            for (int c = 0; c < d; ++c) acc[c] = tmp[c] * norm;
+            for (int c = 0; c < d; ++c) acc[c] = tmp[c] * norm * (signs ? signs[c] : 1.0);
         }
         for (int64_t j = 0; j < nr; ++j) {
             const double p = s[ns + j] / z;

@@ -316,3 +316,46 @@ def test_grouped_query_heads_share_the_cache(oracle):
         o1, m1, _ = oracle.chunk_attention(q[:, h:h + 1], kc[:, h // 3:h // 3 + 1], vc[:, h // 3:h // 3 + 1],
                                            kr[:, h // 3:h // 3 + 1], vr[:, h // 3:h // 3 + 1], 2, 1)
         assert np.array_equal(o1[:, 0], out[:, h]) and np.array_equal(m1[0], mass[h])
+
+
+def test_randomised_rotation_against_dense_matrices(oracle):
+    """Sign vector of the randomised Hadamard rotation: the cache basis is x -> Hn (signs * x).  With the
+    cached keys / values rotated by an explicit dense matrix here and no quantization error (step 0), the
+    result must be textbook attention in the original basis: a sign dropped on the query, on the output,
+    or applied after the Hadamard matrix instead of before it breaks the equality."""
+    rng = np.random.default_rng(33)
+    d, m, ns, nr = 32, 6, 11, 4
+    signs = np.where(rng.random(d) < 0.5, -1.0, 1.0)
+    assert 0 < (signs < 0).sum() < d
+    rot = np.diag(signs) @ (sylvester(d) / np.sqrt(d))          # row vector x -> x @ rot
+    q, ks, vs = rng.standard_normal((m, d)), rng.standard_normal((ns, d)), rng.standard_normal((ns, d))
+    kr, vr = rng.standard_normal((nr, d)), rng.standard_normal((nr, d))
+    out, mass = oracle.attention(q, ks @ rot, np.zeros((ns, 1)), vs @ rot, kr, vr, correction=1, signs=signs)
+    p = softmax(np.concatenate([q @ ks.T, q @ kr.T], axis=1) / np.sqrt(d), axis=1)
+    assert np.allclose(out, p @ np.concatenate([vs, vr]), rtol=1e-11, atol=1e-12)
+    assert np.allclose(mass, p[:, :ns].sum(axis=1), rtol=1e-12)
+    # without the signs the same call is wrong (the pin above is not vacuous)
+    bad, _ = oracle.attention(q, ks @ rot, np.zeros((ns, 1)), vs @ rot, kr, vr, correction=1)
+    assert not np.allclose(bad, out, atol=1e-3)
+
+
+def test_randomised_rotation_in_the_quantizer(oracle):
+    """Codes written with a sign vector decode to within half a step of the densely rotated input, per
+    rotated channel, and un-rotate to the input within the same bound times sqrt(d)."""
+    rng = np.random.default_rng(34)
+    d, rows = 64, 9
+    signs = np.where(rng.random(d) < 0.5, -1.0, 1.0)
+    rot = np.diag(signs) @ (sylvester(d) / np.sqrt(d))
+    x = rng.standard_normal((rows, d)) * np.exp(rng.standard_normal((1, d)))     # uneven channels
+    for bits in (2, 4):
+        codes, scale, zero = oracle.quantize(x, bits, signs=signs)
+        y = x @ rot
+        yhat = (codes.astype(np.float64) - zero.astype(np.float64)) * scale.astype(np.float64)
+        assert np.all(np.abs(yhat - y) <= 0.5 * scale.astype(np.float64) * (1 + 1e-6) + 1e-9)
+        assert np.all(np.abs(yhat @ rot.T - x).max(axis=1) <= 0.5 * scale[:, 0] * np.sqrt(d) * (1 + 1e-6))
+        plain, _, _ = oracle.quantize(x, bits)
+        assert not np.array_equal(plain, codes)
+    # all-plus signs are the plain rotation, bit for bit
+    a = oracle.quantize(x, 2, signs=np.ones(d))
+    b = oracle.quantize(x, 2)
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))

@@ -96,6 +96,15 @@ int64_t kvq_cache_len(const kvq_cache *cache);
 kvq_status kvq_cache_reset(kvq_cache *cache);
 kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len);
 
+/* Randomised Hadamard rotation (rotation paragraph of the method section: the rotation applied to keys and
+ * queries is a Hadamard matrix combined with random signs).  negate: host array [head_dim]; a nonzero entry c
+ * gives channel c the sign -1, so that vectors are mapped x -> Hn (s * x) before quantization, queries the
+ * same way, and the cached part of the output is mapped back with the transpose.  Null restores the plain
+ * rotation (all +1), which is also the state of a new cache.  Drawing the signs is the caller's business.
+ * Allowed only while the cache holds no token (KVQ_ERR_INVALID_ARG otherwise): stored codes belong to the
+ * rotation they were written with.  Exported codes are in the order of the rotated channels either way. */
+kvq_status kvq_cache_set_rotation_signs(kvq_cache *cache, const uint8_t *negate);
+
 /* Sliding window (the cached-chunk window of chunk-wise video generation): forget the n_tokens oldest
  * tokens (0 <= n_tokens <= len; host-side counters only).  The storage is a ring of 32-token tiles, so the
  * space is reused by later appends; positions in kvq_chunk_attention and kvq_cache_export count from the

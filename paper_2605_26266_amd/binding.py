@@ -21,7 +21,7 @@ KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
 # Every symbol declared in include/kvq.h.
 EXPORTED = (
     "kvq_cache_bytes", "kvq_cache_create", "kvq_cache_destroy", "kvq_cache_len", "kvq_cache_reset",
-    "kvq_cache_truncate", "kvq_cache_evict", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
+    "kvq_cache_truncate", "kvq_cache_evict", "kvq_cache_set_rotation_signs", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
     "kvq_chunk_attention_ex",
     "kvq_cache_export", "kvq_status_string", "kvq_version",
 )
@@ -67,6 +67,7 @@ def lib() -> ctypes.CDLL:
     L.kvq_cache_reset.argtypes = [vp]
     L.kvq_cache_truncate.argtypes = [vp, i64]
     L.kvq_cache_evict.argtypes = [vp, i64]
+    L.kvq_cache_set_rotation_signs.argtypes = [vp, ctypes.c_char_p]
     L.kvq_quantize_append.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     att = [vp, i64, i64, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp, vp, vp]
     L.kvq_chunk_attention.argtypes = att
@@ -162,6 +163,17 @@ def kvq_cache_truncate(cache: Cache, new_len: int) -> None:
 
 def kvq_cache_evict(cache: Cache, n_tokens: int) -> None:
     _check(lib().kvq_cache_evict(cache.handle, int(n_tokens)), "kvq_cache_evict")
+
+
+def kvq_cache_set_rotation_signs(cache: Cache, negate) -> None:
+    """negate: None or a sequence of head_dim truthy/falsy entries (truthy = sign -1)."""
+    buf = None
+    if negate is not None:
+        flags = bytes(1 if x else 0 for x in negate)
+        if len(flags) != cache.desc.head_dim:
+            raise ValueError("negate must have head_dim entries")
+        buf = flags
+    _check(lib().kvq_cache_set_rotation_signs(cache.handle, buf), "kvq_cache_set_rotation_signs")
 
 
 def _tok_head_strides(t: torch.Tensor):

@@ -101,6 +101,7 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
     v.head_dim = desc->head_dim;
     v.bits = desc->bits;
     v.io_dtype = desc->io_dtype;
+    for (uint32_t &w : v.sign_mask) w = 0u;
     *out = c;
     return KVQ_OK;
 }
@@ -114,6 +115,17 @@ kvq_status kvq_cache_reset(kvq_cache *cache)
     if (!cache) return KVQ_ERR_INVALID_ARG;
     cache->len = 0;
     cache->base = 0;
+    return KVQ_OK;
+}
+
+kvq_status kvq_cache_set_rotation_signs(kvq_cache *cache, const uint8_t *negate)
+{
+    if (!cache) return KVQ_ERR_INVALID_ARG;
+    if (cache->len != 0) return KVQ_ERR_INVALID_ARG;   // codes already stored belong to the old rotation
+    for (uint32_t &w : cache->view.sign_mask) w = 0u;
+    if (negate)
+        for (int c = 0; c < cache->desc.head_dim; ++c)
+            if (negate[c]) cache->view.sign_mask[c >> 5] |= 1u << (c & 31);
     return KVQ_OK;
 }
 

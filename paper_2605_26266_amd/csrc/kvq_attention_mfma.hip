@@ -141,6 +141,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         float nu = 0.0f;
 #pragma unroll
         for (int i = 0; i < kPrepCh; ++i) nu = fmaf(x[i], x[i], nu);
+        // Randomised rotation: the channel signs come before the Hadamard matrix.
+        if (has_signs(a.cv))
+#pragma unroll
+        for (int w = 0; w < kPrepCh / 32; ++w) {
+            const uint32_t sg = sign_bits_from(a.cv, ppart * kPrepCh + 32 * w);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) x[32 * w + i] = flip_sign(x[32 * w + i], sg >> i);
+        }
 #pragma unroll
         for (int h = 1; h < kPrepCh; h <<= 1) {
 #pragma unroll
@@ -758,6 +766,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             // Hn^T (tau 1) = tau sqrt(d) e_0: only channel 0 (lane half 0, block 0, register 0) sees it.
             const float tau_all = tau[rb] + xhalf(tau[rb]);
             if (hh == 0) o[0][rb][0] -= tau_all * 11.313708498984761f;
+            // The transpose of the randomised rotation ends with the channel signs.
+            if (has_signs(a.cv))
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t sg = a.cv.sign_mask[b] >> (4 * hh);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[b][rb][v] = flip_sign(o[b][rb][v], sg >> (8 * (v >> 2) + (v & 3)));
+            }
         }
     }
 

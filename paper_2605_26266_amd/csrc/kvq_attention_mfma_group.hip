@@ -172,6 +172,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 x[8 * i + 2 * j + 1] = __uint_as_float(ws[j] & 0xffff0000u);
             }
         }
+        // Randomised rotation: the channel signs come before the Hadamard matrix.
+        if (has_signs(a.cv))
+#pragma unroll
+        for (int i = 0; i < D; ++i) x[i] = flip_sign(x[i], a.cv.sign_mask[i >> 5] >> (i & 31));
 #pragma unroll
         for (int h = 1; h < D; h <<= 1) {
 #pragma unroll
@@ -787,6 +791,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                     const float own = o[b][rb][v], other = xhalf(own);
                     o[b][rb][v] = (hh ? other - own : own + other) * 0.088388347648318f;
                 }
+            // The transpose of the randomised rotation ends with the channel signs.
+            if (has_signs(a.cv))
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t sg = a.cv.sign_mask[b] >> (4 * hh);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[b][rb][v] = flip_sign(o[b][rb][v], sg >> (8 * (v >> 2) + (v & 3)));
+            }
         }
     }
 

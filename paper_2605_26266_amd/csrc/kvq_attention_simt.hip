@@ -85,7 +85,8 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     const T *qp = static_cast<const T *>(a.q) + row * a.q_stride_token + (int64_t)qhead * a.q_stride_head;
     const float qc = Io<T>::load(qp + c);
     q_raw[c] = qc;
-    q_rot[c] = qc;
+    const uint32_t sign_c = sign_bits_from(cv, c);   // randomised rotation x -> Hn (s * x): bit 0 set means s_c = -1
+    q_rot[c] = flip_sign(qc, sign_c);
     fwht_lds<D>(q_rot, c);
     q_rot[c] *= norm;
     const bool fp8_meta = cv.meta_format == KVQ_META_FP8_BF16;
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     __syncthreads();
     scratch[c] = acc;
     fwht_lds<D>(scratch, c);
-    acc = scratch[c] * norm;
+    acc = flip_sign(scratch[c] * norm, sign_c);
     __syncthreads();
     for (int64_t base = 0; base < n_vis; base += D) {
         const int64_t j = base + c;

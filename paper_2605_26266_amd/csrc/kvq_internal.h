@@ -45,7 +45,28 @@ struct CacheView {
     int32_t group_size, meta_format;
     uint8_t *k_scale8, *v_scale8;    // [H][cap32][G]  FP8 E4M3 encodings
     uint16_t *k_zero16, *v_zero16;   // [H][cap32][G]  BF16 encodings
+    // Randomised Hadamard rotation x -> Hn (s * x): bit c of the mask set means s_c = -1.  All zero is the
+    // plain rotation.
+    uint32_t sign_mask[4];
 };
+
+// Sign bits of the channels first .. first + 31 - (first mod 32), bit 0 = channel `first`.
+__device__ inline uint32_t sign_bits_from(const CacheView &cv, int first)
+{
+    const int w = first >> 5;
+    const uint32_t m = w == 0 ? cv.sign_mask[0] : w == 1 ? cv.sign_mask[1] : w == 2 ? cv.sign_mask[2] : cv.sign_mask[3];
+    return m >> (first & 31);
+}
+// Uniform over the grid (kernel argument): lets a kernel skip the sign flips of the plain rotation.
+__device__ inline bool has_signs(const CacheView &cv)
+{
+    return (cv.sign_mask[0] | cv.sign_mask[1] | cv.sign_mask[2] | cv.sign_mask[3]) != 0u;
+}
+__device__ inline float flip_sign(float x, uint32_t bit0) { return __uint_as_float(__float_as_uint(x) ^ (bit0 << 31)); }
+__device__ inline double flip_sign(double x, uint32_t bit0)
+{
+    return __hiloint2double(__double2hiint(x) ^ (int)(bit0 << 31), __double2loint(x));
+}
 
 // FP8 E4M3 (bias 7, 3 mantissa bits, subnormals m * 2^-9, no infinities) -> float.  Scales are never
 // negative and never the NaN encoding.

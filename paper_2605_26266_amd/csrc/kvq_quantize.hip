@@ -149,6 +149,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
         if (valid) {
             const T *src = (pass == 0 ? k : v) + (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * EPL;
             Vec<T>::template load<EPL>(src, x);
+            if (has_signs(cv)) {   // signs of the randomised rotation
+                const uint32_t sg = sign_bits_from(cv, l8 * EPL);
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) x[i] = flip_sign(x[i], sg >> i);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) x[i] = 0.0;
@@ -367,6 +372,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
         double x[16];
         if (pass == 0) raw_k.widen(x);
         else raw_v.widen(x);
+        if (has_signs(cv)) {
+            const uint32_t sg = sign_bits_from(cv, l8 * 16);   // signs of the randomised rotation
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = flip_sign(x[i], sg >> i);
+        }
 #pragma unroll
         for (int h = 1; h < 16; h <<= 1) {   // channel bits 0..3
 #pragma unroll

@@ -38,7 +38,7 @@ def export_np(cache: B.Cache, which: int, start: int = 0, count: int = None):
     return codes.cpu().numpy(), scales.cpu().numpy(), zeros.cpu().numpy()
 
 
-def assert_quantized_equal(cache: B.Cache, k: np.ndarray, v: np.ndarray, heads=None, start: int = 0):
+def assert_quantized_equal(cache: B.Cache, k: np.ndarray, v: np.ndarray, heads=None, start: int = 0, signs=None):
     """Bit-exact comparison of the exported cache rows [start, start+n) with the oracle's quantizer.
 
     k, v: float32 [n][heads_in_k][d] holding exactly the appended values for `heads` (default all)."""
@@ -51,7 +51,7 @@ def assert_quantized_equal(cache: B.Cache, k: np.ndarray, v: np.ndarray, heads=N
         codes, scales, zeros = export_np(cache, which, start, n)
         scales, zeros = scales.reshape(scales.shape[0], n, -1), zeros.reshape(zeros.shape[0], n, -1)
         for j, h in enumerate(hs):
-            oc, osc, oz = oracle.quantize(x[:, j, :].astype(np.float64), bits, group, True, fp8_meta)
+            oc, osc, oz = oracle.quantize(x[:, j, :].astype(np.float64), bits, group, True, fp8_meta, signs)
             assert np.array_equal(codes[h], oc), "codes differ: tensor %d head %d (%d elements)" % (
                 which, h, int(np.sum(codes[h] != oc)))
             bad = np.nonzero(np.any(scales[h].view(np.uint32) != osc.view(np.uint32), axis=1))[0]

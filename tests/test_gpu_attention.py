@@ -349,6 +349,45 @@ def test_grouped_query_heads_and_causal_block(P, io, group, fp8, causal):
         P.run_gpu_attention(cache, q_all[:100], kr, vr, io, causal=True)
 
 
+@pytest.mark.parametrize("name,io,group,fp8", [("small", "bf16", None, False), ("small", "bf16", 32, True),
+                                               ("small", "bf16", 64, True), ("small", "fp32", None, False),
+                                               ("tiny", "fp32", None, False)])
+def test_randomised_rotation_signs(P, name, io, group, fp8):
+    """Sign vector of the randomised Hadamard rotation on every kernel: the quantize kernels (head_dim 128
+    and generic), the per-token and group-wise matrix-core attention kernels and the vector kernel."""
+    import oracle
+    from dataclasses import replace
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = replace(wl.WORKLOADS[name], io_dtype=io)
+    d, heads, n_cached = w.head_dim, min(2, w.num_heads), min(333, w.chunk_tokens - 3)
+    rng = np.random.default_rng(77)
+    negate = rng.random(d) < 0.5
+    signs = np.where(negate, -1.0, 1.0)
+    cache = P.make_cache(w, n_cached + 64, heads=heads, group=group, fp8_meta=fp8)
+    B.kvq_cache_set_rotation_signs(cache, negate)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(kc, io), P.to_dev(vc, io))
+    P.assert_quantized_equal(cache, kc, vc, signs=signs)
+    with pytest.raises(B.KvqError):                       # stored codes belong to the rotation they were written with
+        B.kvq_cache_set_rotation_signs(cache, None)
+    q = wl.chunk_q(w, heads=range(heads))[:150]
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=min(70, w.chunk_tokens))
+    tol = P.TOL_OUT_BF16 if io == "bf16" else P.TOL_OUT_FP32
+    for correction in (0, 1):
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, w.bits, correction, group=group, fp8_meta=fp8,
+                                                  signs=signs)
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, io, correction=correction)
+        P.assert_attention_close(out, mass, ref, mass_ref, tol, "signs, correction %d" % correction)
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr[:0], vr[:0], w.bits, 1, group=group, fp8_meta=fp8, signs=signs)
+    out, mass = P.run_gpu_attention(cache, q, None, None, io)
+    P.assert_attention_close(out, mass, ref, mass_ref, tol, "signs, cache only")
+    # back to the plain rotation on the emptied cache
+    B.kvq_cache_reset(cache)
+    B.kvq_cache_set_rotation_signs(cache, None)
+    B.kvq_quantize_append(cache, P.to_dev(kc, io), P.to_dev(vc, io))
+    P.assert_quantized_equal(cache, kc, vc)
+
+
 def test_argument_errors(P):
     from paper_2605_26266_amd import binding as B, workloads as wl
     w = wl.WORKLOADS["small"]

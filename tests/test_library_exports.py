@@ -61,6 +61,7 @@ def test_null_handles_are_rejected_not_dereferenced(B):
     assert L.kvq_cache_reset(None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_cache_truncate(None, 0) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_cache_evict(None, 0) == B.KVQ_ERR_INVALID_ARG
+    assert L.kvq_cache_set_rotation_signs(None, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_quantize_append(None, None, None, 4, 128, 128, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_chunk_attention(None, 0, 0, None, None, None, 1, 1, 128, 128, 0.0, 1, None, None, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_cache_export(None, 0, 0, 0, None, None, None, None) == B.KVQ_ERR_INVALID_ARG
@@ -78,6 +79,8 @@ def test_host_side_cache_object_without_a_gpu(B):
     assert L.kvq_cache_truncate(handle, 1) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_cache_evict(handle, 1) == B.KVQ_ERR_INVALID_ARG       # nothing to evict
     assert L.kvq_cache_evict(handle, 0) == B.KVQ_OK
+    assert L.kvq_cache_set_rotation_signs(handle, bytes([1, 0] * 64)) == B.KVQ_OK
+    assert L.kvq_cache_set_rotation_signs(handle, None) == B.KVQ_OK
     assert L.kvq_cache_create(ctypes.byref(desc), ctypes.c_void_p(0x10000010), 1 << 20, ctypes.byref(ctypes.c_void_p())) \
         == B.KVQ_ERR_INVALID_ARG                                         # storage not 256-byte aligned
     assert L.kvq_cache_create(ctypes.byref(desc), fake, 16, ctypes.byref(ctypes.c_void_p())) == B.KVQ_ERR_INVALID_ARG

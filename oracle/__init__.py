@@ -39,6 +39,7 @@ def _load():
     fp = ctypes.POINTER(ctypes.c_float)
     bp = ctypes.POINTER(ctypes.c_uint8)
     i64, ci, cd = ctypes.c_int64, ctypes.c_int, ctypes.c_double
+    lib.kvqo_diagnostics.argtypes = [ci, ci, i64, i64, i64, dp, dp, dp, dp, dp, dp, dp, dp, cd, ci, ci, dp, dp]
     lib.kvqo_num_threads.restype = ci
     lib.kvqo_hadamard.argtypes = [ci, dp, dp]
     lib.kvqo_quantize_rows.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp]
@@ -209,3 +210,44 @@ def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: 
             mass[h] = p
         quantized.append(dict(k_codes=kc, k_scale=ks, k_zero=kz, v_codes=vc, v_scale=vs, v_zero=vz))
     return out, mass, quantized
+
+
+def diagnostics(q, khat, kstep, vhat, kref, vref, kr, vr, sigma: Optional[float] = None, correction: int = 1,
+                rotate: bool = True, signs=None) -> np.ndarray:
+    """One head.  Quantized (optionally corrected) attention against attention over the unquantized
+    cache kref, vref [ns][d]: returns [m][4] = (P_S, P^_S, JSD(p, p^) in nats over all keys, output MSE)."""
+    q = _d(q)
+    m, d = q.shape
+    khat, vhat = _d(khat).reshape(-1, d), _d(vhat).reshape(-1, d)
+    kref, vref = _d(kref).reshape(-1, d), _d(vref).reshape(-1, d)
+    kr, vr = _d(kr).reshape(-1, d), _d(vr).reshape(-1, d)
+    ns, nr = khat.shape[0], kr.shape[0]
+    assert kref.shape[0] == ns and vref.shape[0] == ns and vhat.shape[0] == ns
+    kstep = _d(kstep).reshape(ns, -1) if ns else np.zeros((0, 1))
+    G = kstep.shape[1] if ns else 1
+    sigma = 1.0 / np.sqrt(d) if sigma is None else float(sigma)
+    sg = _signs(signs, d) if rotate else None
+    diag = np.empty((m, 4), dtype=np.float64)
+    dp = ctypes.c_double
+    rc = _load().kvqo_diagnostics(d, d // G, m, ns, nr, _p(q, dp), _p(khat, dp), _p(kstep, dp), _p(vhat, dp),
+                                  _p(kref, dp), _p(vref, dp), _p(kr, dp), _p(vr, dp), sigma, int(correction),
+                                  int(rotate), None if sg is None else _p(sg, dp), _p(diag, dp))
+    if rc:
+        raise ValueError("diagnostics: bad arguments")
+    return diag
+
+
+def chunk_diagnostics(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
+                      sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True,
+                      fp8_meta: bool = False, signs=None) -> np.ndarray:
+    """[token][head][d] inputs: quantize the cached K/V per head, then diagnostics -> [heads][m][4]."""
+    q = np.asarray(q)
+    m, heads, d = q.shape
+    out = np.empty((heads, m, 4), dtype=np.float64)
+    for h in range(heads):
+        kc, ks, kz = quantize(np.asarray(k_cached)[:, h, :], bits, group, rotate, fp8_meta, signs)
+        vc, vs, vz = quantize(np.asarray(v_cached)[:, h, :], bits, group, rotate, fp8_meta, signs)
+        out[h] = diagnostics(q[:, h, :], dequantize(kc, ks, kz), ks, dequantize(vc, vs, vz),
+                             np.asarray(k_cached)[:, h, :], np.asarray(v_cached)[:, h, :],
+                             np.asarray(k_cur)[:, h, :], np.asarray(v_cur)[:, h, :], sigma, correction, rotate, signs)
+    return out

@@ -439,3 +439,95 @@ int kvqo_attention_masked(int d, int group, int64_t m, int64_t ns, int64_t nr,
     }
     return failed;
 }
+
+/*
+ * Attention-level diagnostics of the bias and of its repair (attention stealing,
+ * Eq. "attn_stealing"; appendices "Attention JSD Distributions" and "Attention
+ * Output MSE"): the quantized (optionally corrected) attention of one head
+ * against attention over the unquantized cache, on the same queries and keys.
+ *
+ *   p   = softmax([sigma q.kref_i | sigma q.kr_j])          unquantized cache
+ *   p^  = softmax([sigma q~.k^_i - b_i | sigma q.kr_j])      quantized cache
+ *   diag[r][0] = P_S   = sum_{i in S} p_i
+ *   diag[r][1] = P^_S  = sum_{i in S} p^_i      (the stealing is diag[1] - diag[0])
+ *   diag[r][2] = JSD(p, p^) = KL(p || mix)/2 + KL(p^ || mix)/2, mix = (p + p^)/2,
+ *                natural logarithm, over all ns + nr keys; terms with a zero
+ *                probability contribute 0
+ *   diag[r][3] = (1/d) sum_c (o^_c - o_c)^2,  o = sum_i p_i vref_i + sum_j p_j vr_j,
+ *                o^ as kvqo_attention_masked computes it
+ *
+ * kref, vref [ns][d]: the cached keys / values before quantization, in the
+ * original basis.  The other arguments are those of kvqo_attention_masked.
+ */
+int kvqo_diagnostics(int d, int group, int64_t m, int64_t ns, int64_t nr,
+                     const double *q, const double *khat, const double *kstep, const double *vhat,
+                     const double *kref, const double *vref, const double *kr, const double *vr,
+                     double sigma, int correction, int rotate, const double *signs, double *diag)
+{
+    if (d <= 0 || group <= 0 || d % group != 0 || m < 0 || ns < 0 || nr < 0 || ns + nr == 0) return 1;
+    if (rotate && !is_pow2(d)) return 1;
+    if (correction < 0 || correction > 2) return 1;
+    const int G = d / group;
+    const int64_t n = ns + nr;
+    const double norm = inv_sqrt_d(d);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t r = 0; r < m; ++r) {
+        double *buf = (double *)malloc(sizeof(double) * ((size_t)d * 5 + (size_t)n * 2));
+        if (!buf) { failed = 1; continue; }
+        double *qv = buf, *tmp = qv + d, *acc = tmp + d, *oq = acc + d, *oref = oq + d;
+        double *p = oref + d, *ph = p + n;
+        const double *qr = q + r * d;
+        if (rotate) {
+            if (signs) { for (int c = 0; c < d; ++c) tmp[c] = signs[c] * qr[c]; }
+            kvqo_hadamard(d, signs ? tmp : qr, qv);
+            for (int c = 0; c < d; ++c) qv[c] *= norm;
+        } else {
+            memcpy(qv, qr, sizeof(double) * (size_t)d);
+        }
+        /* the two score rows */
+        for (int64_t i = 0; i < ns; ++i) {
+            double dref = 0.0, dq = 0.0;
+            for (int c = 0; c < d; ++c) { dref += qr[c] * kref[i * d + c]; dq += qv[c] * khat[i * d + c]; }
+            p[i] = sigma * dref;
+            ph[i] = sigma * dq - kvqo_correction(d, group, qv, kstep + i * G, sigma, correction);
+        }
+        for (int64_t j = 0; j < nr; ++j) {
+            double dot = 0.0;
+            for (int c = 0; c < d; ++c) dot += qr[c] * kr[j * d + c];
+            p[ns + j] = ph[ns + j] = sigma * dot;
+        }
+        /* two softmaxes */
+        double top = p[0], toph = ph[0], z = 0.0, zh = 0.0;
+        for (int64_t i = 1; i < n; ++i) { if (p[i] > top) top = p[i]; if (ph[i] > toph) toph = ph[i]; }
+        for (int64_t i = 0; i < n; ++i) { p[i] = exp(p[i] - top); z += p[i]; ph[i] = exp(ph[i] - toph); zh += ph[i]; }
+        for (int64_t i = 0; i < n; ++i) { p[i] /= z; ph[i] /= zh; }
+        double ps = 0.0, psh = 0.0, jsd = 0.0;
+        for (int64_t i = 0; i < ns; ++i) { ps += p[i]; psh += ph[i]; }
+        for (int64_t i = 0; i < n; ++i) {
+            const double mix = 0.5 * (p[i] + ph[i]);
+            if (p[i] > 0.0) jsd += 0.5 * p[i] * log(p[i] / mix);
+            if (ph[i] > 0.0) jsd += 0.5 * ph[i] * log(ph[i] / mix);
+        }
+        /* the two outputs */
+        for (int c = 0; c < d; ++c) { acc[c] = 0.0; oref[c] = 0.0; }
+        for (int64_t i = 0; i < ns; ++i)
+            for (int c = 0; c < d; ++c) { acc[c] += ph[i] * vhat[i * d + c]; oref[c] += p[i] * vref[i * d + c]; }
+        if (rotate) {
+            kvqo_hadamard(d, acc, tmp);
+            for (int c = 0; c < d; ++c) oq[c] = tmp[c] * norm * (signs ? signs[c] : 1.0);
+        } else {
+            memcpy(oq, acc, sizeof(double) * (size_t)d);
+        }
+        for (int64_t j = 0; j < nr; ++j)
+            for (int c = 0; c < d; ++c) { oq[c] += ph[ns + j] * vr[j * d + c]; oref[c] += p[ns + j] * vr[j * d + c]; }
+        double mse = 0.0;
+        for (int c = 0; c < d; ++c) mse += (oq[c] - oref[c]) * (oq[c] - oref[c]);
+        diag[r * 4 + 0] = ps;
+        diag[r * 4 + 1] = psh;
+        diag[r * 4 + 2] = jsd;
+        diag[r * 4 + 3] = mse / d;
+        free(buf);
+    }
+    return failed;
+}

@@ -191,6 +191,28 @@ kvq_status kvq_chunk_attention_fp32(const kvq_cache *cache, int64_t cache_start,
                                     void *out, float *mass_cached, void *hip_stream);
 
 /*
+ * Attention-level diagnostics of the bias and of its repair (attention stealing, the equation that defines
+ * Delta P_S; appendices "Attention JSD Distributions" and "Attention Output MSE"): the attention of
+ * kvq_chunk_attention over the quantized window, with the given correction mode (0, 1, 2), compared per
+ * (head, query row) with attention over the same tokens unquantized.
+ * k_ref, v_ref: device [cache_len][num_heads][head_dim], io_dtype, strides of k_cur / v_cur: the keys and
+ * values that were appended at window positions cache_start .. cache_start + cache_len - 1 (the caller kept
+ * them; the library cannot recover them).  Other arguments as for kvq_chunk_attention.
+ * diag: device float [num_heads][m][4], written with
+ *   [0] P_S, the mass on the window under unquantized attention   [1] P_S under quantized attention
+ *       ([1] - [0] is the attention stealing)
+ *   [2] Jensen-Shannon divergence (natural logarithm, in [0, log 2]) between the two weight vectors over all
+ *       cache_len + n_cur keys
+ *   [3] mean over channels of the squared difference of the two attention outputs.
+ * Runs on the fp32 vector kernel (two passes over the keys per row): a measuring tool, not a fast path.
+ */
+kvq_status kvq_attention_diagnostics(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
+                                     const void *q, const void *k_ref, const void *v_ref,
+                                     const void *k_cur, const void *v_cur, int64_t m, int64_t n_cur,
+                                     int64_t stride_token, int64_t stride_head, float softmax_scale,
+                                     int correction, float *diag, void *hip_stream);
+
+/*
  * Canonical view of cached tokens [start, start + count), for parity checks and dump/restore.
  * which: 0 = keys, 1 = values.  codes: device uint8 [num_heads][count][head_dim], one code per
  * byte, channel order of the rotated vector.  scales, zeros: device float [num_heads][count][G],

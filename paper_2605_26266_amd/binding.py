@@ -22,7 +22,7 @@ KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
 EXPORTED = (
     "kvq_cache_bytes", "kvq_cache_create", "kvq_cache_destroy", "kvq_cache_len", "kvq_cache_reset",
     "kvq_cache_truncate", "kvq_cache_evict", "kvq_cache_set_rotation_signs", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
-    "kvq_chunk_attention_ex",
+    "kvq_chunk_attention_ex", "kvq_attention_diagnostics",
     "kvq_cache_export", "kvq_status_string", "kvq_version",
 )
 
@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
     L.kvq_chunk_attention.argtypes = att
     L.kvq_chunk_attention_fp32.argtypes = att
     L.kvq_chunk_attention_ex.argtypes = att[:12] + [ctypes.POINTER(kvq_attention_opts)] + att[12:]
+    L.kvq_attention_diagnostics.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp, vp]
     L.kvq_cache_export.argtypes = [vp, ci, i64, i64, vp, vp, vp, vp]
     L.kvq_status_string.argtypes = [ci]
     L.kvq_status_string.restype = ctypes.c_char_p
@@ -241,6 +242,31 @@ def kvq_chunk_attention_ex(cache: Cache, cache_start: int, cache_len: int, q: to
                                         _ptr(v_cur), q.shape[0], n_cur, st, sh, float(softmax_scale), int(correction),
                                         ctypes.byref(opts), out.data_ptr(), _ptr(mass_cached), _stream(stream)),
            "kvq_chunk_attention_ex")
+
+
+def kvq_attention_diagnostics(cache: Cache, cache_start: int, cache_len: int, q: torch.Tensor,
+                              k_ref: Optional[torch.Tensor], v_ref: Optional[torch.Tensor],
+                              k_cur: Optional[torch.Tensor], v_cur: Optional[torch.Tensor], diag: torch.Tensor,
+                              softmax_scale: float = 0.0, correction: int = 1,
+                              stream: Optional[torch.cuda.Stream] = None) -> None:
+    """diag: float32 [heads][m][4] = (P_S unquantized, P_S quantized, JSD in nats, output MSE) per row.
+    k_ref / v_ref: the unquantized tokens of the window [cache_len][heads][d]; all [token][head][d]
+    tensors must share dtype and strides."""
+    tensors = [t for t in (k_ref, v_ref, k_cur, v_cur) if t is not None and t.shape[0] > 0]
+    if q.dtype != cache.torch_dtype or any(t.dtype != cache.torch_dtype for t in tensors):
+        raise ValueError("tensors must be in the cache's io dtype")
+    if len({_tok_head_strides(t) for t in tensors + [q]}) > 1:
+        raise ValueError("q, k_ref, v_ref, k_cur and v_cur must share strides")
+    if k_ref is not None and (k_ref.shape[0] != cache_len or v_ref is None or v_ref.shape[0] != cache_len):
+        raise ValueError("k_ref and v_ref must hold cache_len tokens")
+    if diag.dtype != torch.float32 or not diag.is_contiguous() or diag.numel() != cache.desc.num_heads * q.shape[0] * 4:
+        raise ValueError("diag must be a contiguous float32 [heads][m][4] tensor")
+    st, sh = _tok_head_strides(q)
+    n_cur = 0 if k_cur is None else k_cur.shape[0]
+    _check(lib().kvq_attention_diagnostics(cache.handle, int(cache_start), int(cache_len), q.data_ptr(), _ptr(k_ref),
+                                           _ptr(v_ref), _ptr(k_cur), _ptr(v_cur), q.shape[0], n_cur, st, sh,
+                                           float(softmax_scale), int(correction), diag.data_ptr(), _stream(stream)),
+           "kvq_attention_diagnostics")
 
 
 def kvq_chunk_attention_fp32(cache: Cache, cache_start: int, cache_len: int, q: torch.Tensor,

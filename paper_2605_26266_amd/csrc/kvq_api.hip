@@ -170,8 +170,10 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
                                    const void *q, const void *k_cur, const void *v_cur, int64_t m,
                                    int64_t n_cur, int64_t stride_token, int64_t stride_head,
                                    float softmax_scale, int correction, void *out, float *mass_cached,
-                                   void *hip_stream, bool force_vector, const kvq_attention_opts *opts = nullptr)
+                                   void *hip_stream, bool force_vector, const kvq_attention_opts *opts = nullptr,
+                                   const void *k_ref = nullptr, const void *v_ref = nullptr, float *diag = nullptr)
 {
+    // diag != nullptr: the diagnostics call (no out / mass_cached; k_ref, v_ref hold the cached tokens unquantized)
     kvq_attention_opts o = {1, 0, stride_token, stride_head};
     if (opts) {
         o = *opts;
@@ -190,14 +192,17 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     if (!(softmax_scale >= 0.0f) || !(softmax_scale < 3.0e38f)) return KVQ_ERR_INVALID_ARG;
     if (m == 0) return KVQ_OK;
     const kvq_cache_desc &d = cache->desc;
-    if (!tensor_ok(q, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype) ||
-        !tensor_ok(out, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype))
+    if (!tensor_ok(q, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype)) return KVQ_ERR_INVALID_ARG;
+    if (!diag && !tensor_ok(out, o.q_stride_token, o.q_stride_head, d.head_dim, d.io_dtype)) return KVQ_ERR_INVALID_ARG;
+    if (diag && cache_len > 0 && (!tensor_ok(k_ref, stride_token, stride_head, d.head_dim, d.io_dtype) ||
+                                  !tensor_ok(v_ref, stride_token, stride_head, d.head_dim, d.io_dtype)))
         return KVQ_ERR_INVALID_ARG;
+    if (diag && reinterpret_cast<uintptr_t>(diag) % 4 != 0) return KVQ_ERR_INVALID_ARG;
     if (n_cur > 0 && (!tensor_ok(k_cur, stride_token, stride_head, d.head_dim, d.io_dtype) ||
                       !tensor_ok(v_cur, stride_token, stride_head, d.head_dim, d.io_dtype)))
         return KVQ_ERR_INVALID_ARG;
     if (mass_cached && reinterpret_cast<uintptr_t>(mass_cached) % 4 != 0) return KVQ_ERR_INVALID_ARG;
-    if (out == q || out == k_cur || out == v_cur) return KVQ_ERR_INVALID_ARG;
+    if (!diag && (out == q || out == k_cur || out == v_cur)) return KVQ_ERR_INVALID_ARG;
     if (m > ((int64_t)1 << 31) - 256 || n_cur > ((int64_t)1 << 31) - 256) return KVQ_ERR_INVALID_ARG;
 
     kvq::AttentionArgs a;
@@ -225,6 +230,7 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
                              d.group_size == d.head_dim;   // one (scale, zero-point) per token, either format
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (diag) return kvq::launch_diagnostics_simt(a, k_ref, v_ref, diag, s) == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
     const bool group_matrix_path = !force_vector && kvq::attention_mfma_group_supported(cache->view);
     const hipError_t e = matrix_path         ? kvq::launch_attention_mfma(a, s)
                          : group_matrix_path ? kvq::launch_attention_mfma_group(a, s)
@@ -260,6 +266,16 @@ kvq_status kvq_chunk_attention_ex(const kvq_cache *cache, int64_t cache_start, i
 {
     return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
                             softmax_scale, correction, out, mass_cached, hip_stream, false, opts);
+}
+
+kvq_status kvq_attention_diagnostics(const kvq_cache *cache, int64_t cache_start, int64_t cache_len, const void *q,
+                                     const void *k_ref, const void *v_ref, const void *k_cur, const void *v_cur,
+                                     int64_t m, int64_t n_cur, int64_t stride_token, int64_t stride_head,
+                                     float softmax_scale, int correction, float *diag, void *hip_stream)
+{
+    if (!diag) return KVQ_ERR_INVALID_ARG;
+    return attention_common(cache, cache_start, cache_len, q, k_cur, v_cur, m, n_cur, stride_token, stride_head,
+                            softmax_scale, correction, nullptr, nullptr, hip_stream, true, nullptr, k_ref, v_ref, diag);
 }
 
 kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count, uint8_t *codes,

@@ -149,6 +149,10 @@ struct AttentionArgs {
 };
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream);
+// Per (head, row) [P_S unquantized, P_S quantized, JSD, output MSE] against the unquantized cached k_ref / v_ref
+// ([cache_len][H][d], strides of k_cur); a.out and a.mass_cached are not used.
+hipError_t launch_diagnostics_simt(const AttentionArgs &a, const void *k_ref, const void *v_ref, float *diag,
+                                   hipStream_t stream);
 // Matrix-core kernel for caches with several FP8/BF16 (scale, zero-point) groups per token.
 bool attention_mfma_group_supported(const CacheView &cv);
 hipError_t launch_attention_mfma_group(const AttentionArgs &a, hipStream_t stream);

@@ -406,3 +406,53 @@ def test_argument_errors(P):
     with pytest.raises(B.KvqError):
         B.kvq_chunk_attention(cache, 0, 64, q, None, None, out, correction=3)
     B.kvq_chunk_attention(cache, 0, 64, q[:0], None, None, out[:0])   # m == 0 is a no-op
+
+
+@pytest.mark.parametrize("name,io,bits,group,fp8", [("small", "bf16", 2, None, False), ("small", "bf16", 4, 32, True),
+                                                    ("tiny", "fp32", 2, None, False)])
+def test_attention_diagnostics(P, name, io, bits, group, fp8):
+    """kvq_attention_diagnostics against the oracle: both cached masses to the bar of P_S, the divergence and
+    the output MSE to 2e-3 relative (they are sums of squares of small differences taken in fp32)."""
+    import oracle
+    from dataclasses import replace
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = replace(wl.WORKLOADS[name], io_dtype=io, bits=bits)
+    heads = min(2, w.num_heads)
+    n_cached, n_cur, m = min(300, w.chunk_tokens), min(150, w.chunk_tokens), min(70, w.chunk_tokens)
+    cache = P.make_cache(w, n_cached + 40, heads=heads, group=group, fp8_meta=fp8)
+    pad_k, pad_v = wl.chunk_kv(w, 2, heads=range(heads), n_tokens=40)      # the window starts inside a tile
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(pad_k, io), P.to_dev(pad_v, io))
+    B.kvq_quantize_append(cache, P.to_dev(kc, io), P.to_dev(vc, io))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.chunk_q(w, heads=range(heads))[:m]
+    qd, kcd, vcd, krd, vrd = (P.to_dev(x, io) for x in (q, kc, vc, kr, vr))
+    for correction in (0, 1, 2):
+        diag = torch.full((heads, m, 4), float("nan"), dtype=torch.float32, device=P.DEV)
+        B.kvq_attention_diagnostics(cache, 40, n_cached, qd, kcd, vcd, krd, vrd, diag, correction=correction)
+        torch.cuda.synchronize()
+        got = diag.cpu().numpy().astype(np.float64)
+        ref = oracle.chunk_diagnostics(q, kc, vc, kr, vr, bits, correction, group=group, fp8_meta=fp8)
+        assert np.all(np.isfinite(got))
+        for col, name_ in ((0, "P_S unquantized"), (1, "P_S quantized")):
+            for g_, r_ in ((got[:, :, col], ref[:, :, col]), (1 - got[:, :, col], 1 - ref[:, :, col])):
+                sel = r_ >= 1e-4
+                assert np.max(np.abs(g_[sel] - r_[sel]) / r_[sel]) <= P.TOL_MASS_REL, name_
+        for col, name_ in ((2, "JSD"), (3, "MSE")):
+            err = np.abs(got[:, :, col] - ref[:, :, col])
+            assert np.all(err <= 2e-3 * ref[:, :, col] + 1e-9), "%s: %.3e" % (name_, float(np.max(err / (ref[:, :, col] + 1e-30))))
+    # the quantized side is what kvq_chunk_attention reports
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, io, cache_start=40, cache_len=n_cached, correction=2, fp32_kernel=True)
+    assert np.allclose(mass, got[:, :, 1], rtol=1e-5, atol=1e-7)
+    # no current block, and no cached window
+    diag = torch.full((heads, m, 4), float("nan"), dtype=torch.float32, device=P.DEV)
+    B.kvq_attention_diagnostics(cache, 40, n_cached, qd, kcd, vcd, None, None, diag)
+    torch.cuda.synchronize()
+    ref = oracle.chunk_diagnostics(q, kc, vc, kr[:0], vr[:0], bits, 1, group=group, fp8_meta=fp8)
+    got = diag.cpu().numpy().astype(np.float64)
+    assert np.allclose(got[:, :, :2], 1.0, atol=1e-6)
+    assert np.all(np.abs(got[:, :, 2:] - ref[:, :, 2:]) <= 2e-3 * ref[:, :, 2:] + 1e-9)
+    B.kvq_attention_diagnostics(cache, 0, 0, qd, None, None, krd, vrd, diag)
+    torch.cuda.synchronize()
+    got = diag.cpu().numpy()
+    assert np.all(got[:, :, :2] == 0.0) and np.all(np.abs(got[:, :, 2:]) <= 1e-9)

@@ -65,6 +65,7 @@ def test_null_handles_are_rejected_not_dereferenced(B):
     assert L.kvq_quantize_append(None, None, None, 4, 128, 128, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_chunk_attention(None, 0, 0, None, None, None, 1, 1, 128, 128, 0.0, 1, None, None, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_cache_export(None, 0, 0, 0, None, None, None, None) == B.KVQ_ERR_INVALID_ARG
+    assert L.kvq_attention_diagnostics(None, 0, 0, None, None, None, None, None, 1, 1, 128, 128, 0.0, 1, None, None) == B.KVQ_ERR_INVALID_ARG
     L.kvq_cache_destroy(None)
 
 

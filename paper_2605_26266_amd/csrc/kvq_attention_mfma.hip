@@ -47,6 +47,17 @@
 // transposed through LDS (token-major operands); scores get no correction.
 #include "kvq_internal.h"
 
+// 1: the rotated query enters the score MFMAs as an f16 high part plus an f16 low part (two MFMAs per
+// slab and row block); 0: high part only.
+#ifndef KVQ_Q_LOW_PART
+#define KVQ_Q_LOW_PART 1
+#endif
+// Number of 16-channel slabs whose low query parts stay in accumulation registers instead of being read
+// from LDS for every key tile (4 registers per slab and 32-row block).
+#ifndef KVQ_Q_LOW_RESIDENT_SLABS
+#define KVQ_Q_LOW_RESIDENT_SLABS 4
+#endif
+
 namespace kvq {
 namespace {
 
@@ -200,7 +211,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const uint32_t hi = pack_f16(v0, v1);
                 const float h0 = f16_lo(hi), h1 = f16_hi(hi);
                 lo[j] = pack_f16(v0 - h0, v1 - h1);
+#if KVQ_Q_LOW_PART
                 const float pair = (h0 + f16_lo(lo[j])) + (h1 + f16_hi(lo[j]));   // both channels share a class
+#else
+                const float pair = h0 + h1;
+#endif
                 ssum_w += pair;
                 ssum += pair * (1.0f / (float)(1 << (2 * key_channel_class<BITS>(8 * i + 2 * j))));
             }
@@ -255,6 +270,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
+
+    constexpr int kLoRes = KVQ_Q_LOW_PART ? KVQ_Q_LOW_RESIDENT_SLABS : 0;
+    u32x4 lo_res[kRB][kLoRes > 0 ? kLoRes : 1];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int s = 0; s < kLoRes; ++s) {
+            lo_res[rb][s] = *reinterpret_cast<const u32x4 *>(q_stage + lo_off + 32 * rb * kQRowWords + 8 * s);
+            asm volatile("" : "+a"(lo_res[rb][s]));
+        }
 
     f32x16 o[4][kRB];
 #pragma unroll
@@ -440,13 +465,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
                 const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
+#if KVQ_Q_LOW_PART
                 u32x4 lo[kRB];
+                if constexpr (SLAB >= kLoRes) {
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                    for (int rb = 0; rb < kRB; ++rb) lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                }
+#endif
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+#if KVQ_Q_LOW_PART
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, lo[rb], sn[rb]);
+                for (int rb = 0; rb < kRB; ++rb) {
+                    if constexpr (SLAB < kLoRes) sn[rb] = mfma_f16(kop, lo_res[rb][SLAB], sn[rb]);
+                    else sn[rb] = mfma_f16(kop, lo[rb], sn[rb]);
+                }
+#endif
             });
         };
         // e = scale_i * raw - reference; returns the tile maximum of e per row block.
@@ -603,9 +637,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 constexpr int SLAB = decltype(s_)::value;
                 // This slab's low query parts are requested now and multiplied one chunk later, so that no
                 // MFMA of the iteration waits for LDS: the high parts and the key codes are in registers.
+#if KVQ_Q_LOW_PART
+                if constexpr (SLAB >= kLoRes) {
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb)
-                    lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                    for (int rb = 0; rb < kRB; ++rb)
+                        lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                }
+#endif
                 if constexpr (SLAB == 5) {  // value codes and key scales for the second half of the iteration
                     const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
 #pragma unroll
@@ -624,17 +662,31 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
                 if constexpr (SLAB >= 1) {
+#if KVQ_Q_LOW_PART
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        if constexpr (SLAB - 1 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][SLAB - 1], sn[rb]);
+                        else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                    }
+#endif
                     exp_chunk(IntC<SLAB - 1>{});
                 }
+#if KVQ_Q_LOW_PART
                 kop_prev = kop;
+                if constexpr (SLAB >= kLoRes) {
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
+                    for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
+                }
+#endif
                 KVQ_CHUNK_FENCE();
             });
+#if KVQ_Q_LOW_PART
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+            for (int rb = 0; rb < kRB; ++rb) {
+                if constexpr (7 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][7], sn[rb]);
+                else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+            }
+#endif
             exp_chunk(IntC<7>{});
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {

@@ -27,14 +27,19 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
     } while (0)
 
 constexpr int kBlocks = 256;   // one workgroup per compute unit
-constexpr int kIters = 2000;
+constexpr int kIters = 5000;    // x kSteps steps per kernel: several milliseconds, so that clocks have settled
+constexpr int kSteps = 32;      // steps per loop iteration
 
 enum Op { kFma, kMul, kAndOr, kShift, kCvtPk, kDot2, kExp2, kMax3 };
 
-// W waves per SIMD; each wave runs kIters x 8 steps of (one 32x32x16 MFMA on one of CH accumulators,
+// W waves per SIMD; each wave runs kIters x kSteps steps of (one 32x32x16 MFMA on one of CH accumulators,
 // then NV independent vector instructions of kind OP).
 // CH = -1: the MFMA takes the constant 0 as its C operand (nothing accumulated, no accumulator read).
-template <int W, int CH, int NV, Op OP>
+// The loop body starts on a 64-byte boundary plus 4 * HEAD bytes: where the instructions fall relative to
+// the 32-byte instruction-fetch blocks changes the time of a dense stream of 8-byte instructions by up to
+// 30 %, so the alignment is fixed rather than left to chance (the padding is at most 15 one-cycle no-ops
+// per kSteps steps).
+template <int W, int CH, int NV, Op OP, int HEAD = 0>
 __global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t mask, uint32_t base)
 {
     f16x8 a, b;
@@ -54,13 +59,16 @@ __global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t ma
     }
     const uint32_t bs = base + threadIdx.x;
     for (int it = 0; it < kIters; ++it) {
+        asm volatile(".p2align 6");
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int p = 0; p < HEAD; ++p) asm volatile("s_nop 0");
+#pragma unroll
+        for (int j = 0; j < kSteps; ++j) {
             if (CH > 0) c[j % (CH > 0 ? CH : 1)] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c[j % (CH > 0 ? CH : 1)], 0, 0, 0);
             if (CH < 0) {
                 f32x16 zero;
                 for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-                c[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, zero, 0, 0, 0);
+                c[j & 7] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, zero, 0, 0, 0);
             }
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -108,10 +116,10 @@ template <typename F> float time_ms(F &&launch)
 }
 
 // ns per step (one MFMA + NV instructions) and per SIMD: with W waves a SIMD completes W steps in that time.
-template <int W, int CH, int NV, Op OP> double step_ns(float *out)
+template <int W, int CH, int NV, Op OP, int HEAD = 0> double step_ns(float *out)
 {
-    const float ms = time_ms([&] { mix_kernel<W, CH, NV, OP><<<kBlocks, 256 * W>>>(out, 0x03000300u, 0x44004400u); });
-    return ms * 1e6 / (kIters * 8.0) / W;
+    const float ms = time_ms([&] { mix_kernel<W, CH, NV, OP, HEAD><<<kBlocks, 256 * W>>>(out, 0x03000300u, 0x44004400u); });
+    return ms * 1e6 / ((double)kIters * kSteps) / W;
 }
 
 template <Op OP> void op_row(float *out, const char *name)
@@ -158,6 +166,8 @@ int main()
     float *out;
     CHECK(hipMalloc(&out, (size_t)kBlocks * 512 * sizeof(float)));
 
+    for (int r = 0; r < 8; ++r) step_ns<1, 4, 8, kFma>(out);   // bring the clocks up before the first figure
+
     printf("## MFMA only: ns per v_mfma_f32_32x32x16_f16 per SIMD (32768 flop each, 1024 SIMDs)\n\n");
     printf("| waves/SIMD | accumulator chains | ns per MFMA | chip TFLOP/s |\n|---|---|---|---|\n");
     {
@@ -177,6 +187,12 @@ int main()
     printf("| 16, no MFMA | %.2f | %.2f |\n", step_ns<1, 0, 16, kFma>(out), step_ns<2, 0, 16, kFma>(out));
     printf("| 12, MFMA with C = 0 | %.2f | %.2f |\n", step_ns<1, -1, 12, kFma>(out), step_ns<2, -1, 12, kFma>(out));
     printf("| 16, MFMA with C = 0 | %.2f | %.2f |\n", step_ns<1, -1, 16, kFma>(out), step_ns<2, -1, 16, kFma>(out));
+
+    printf("\n## The same step (1 MFMA + 8 v_fma_f32, 1 wave/SIMD) with the loop body 0, 4, 8, 28 bytes past a 64-byte boundary\n\n");
+    printf("| offset | ns per step |\n|---|---|\n");
+    printf("| 0 | %.2f |\n| 4 | %.2f |\n| 8 | %.2f |\n| 12 | %.2f |\n| 28 | %.2f |\n", step_ns<1, 4, 8, kFma, 0>(out),
+           step_ns<1, 4, 8, kFma, 1>(out), step_ns<1, 4, 8, kFma, 2>(out), step_ns<1, 4, 8, kFma, 3>(out),
+           step_ns<1, 4, 8, kFma, 7>(out));
 
     printf("\n## Marginal cost of one vector instruction next to MFMAs (step = 1 MFMA + N instr; ns per SIMD)\n\n");
     printf("| instruction | 1w N=8 | 1w N=16 | 1w ns/instr | 2w N=8 | 2w N=16 | 2w ns/instr |\n|---|---|---|---|---|---|---|\n");

@@ -43,6 +43,7 @@ def _load():
     lib.kvqo_num_threads.restype = ci
     lib.kvqo_hadamard.argtypes = [ci, dp, dp]
     lib.kvqo_quantize_rows.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp]
+    lib.kvqo_quantize_cols.argtypes = [i64, ci, ci, ci, dp, bp, fp, fp]
     lib.kvqo_quantize_rows_fp8meta.argtypes = [i64, ci, ci, ci, ci, dp, bp, fp, fp, bp]
     lib.kvqo_e4m3_ceil.argtypes = [cd, bp]
     lib.kvqo_e4m3_ceil.restype = cd
@@ -116,6 +117,22 @@ def quantize(x, bits: int, group: Optional[int] = None, rotate: bool = True, fp8
     return codes, scale, zero
 
 
+def quantize_per_channel(x, bits: int, rotate: bool = True, signs=None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """One block of tokens x [rows][d] -> codes uint8 [rows][d], scale float32 [d], zero float32 [d]: one
+    (scale, zero-point) per channel of the (rotated) vectors, shared by all tokens of the block."""
+    x = _d(x)
+    rows, d = x.shape
+    if signs is not None and rotate:
+        x = np.ascontiguousarray(x * _signs(signs, d)[None, :])
+    codes = np.empty((rows, d), dtype=np.uint8)
+    scale = np.empty((d,), dtype=np.float32)
+    zero = np.empty((d,), dtype=np.float32)
+    if _load().kvqo_quantize_cols(rows, d, bits, int(rotate), _p(x, ctypes.c_double), _p(codes, ctypes.c_uint8),
+                                  _p(scale, ctypes.c_float), _p(zero, ctypes.c_float)):
+        raise ValueError("quantize_per_channel: bad arguments")
+    return codes, scale, zero
+
+
 def e4m3_ceil(x: float) -> Tuple[float, int]:
     """Smallest FP8 E4M3 value >= x (x > 0) and its encoding."""
     b = ctypes.c_uint8(0)
@@ -183,13 +200,16 @@ def attention(q, khat, kstep, vhat, kr, vr, sigma: Optional[float] = None, corre
 
 def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: int = 1,
                     sigma: Optional[float] = None, group: Optional[int] = None, rotate: bool = True,
-                    fp8_meta: bool = False, causal: bool = False, signs=None):
+                    fp8_meta: bool = False, causal: bool = False, signs=None, key_blocks=None):
     """Whole path for [token][head][d] inputs: quantize the cached K/V per head, then attention.
 
     q may have a multiple of the K/V head count (grouped-query attention): query head h uses
     key/value head h // (q_heads // kv_heads).
     Returns (out [m][q_heads][d], P_S [q_heads][m], quantized) where quantized holds the
     per-KV-head codes / scales / zeros of K and V for parity checks.
+    key_blocks: list of block lengths that add up to the cached tokens; the keys of each block are then
+    quantized per channel (one scale / zero-point per channel, shared by the block's tokens), the values
+    per token as always, and k_scale / k_zero are [tokens][d] (each token carries its block's values).
     """
     q = np.asarray(q)
     m, heads, d = q.shape
@@ -200,7 +220,17 @@ def chunk_attention(q, k_cached, v_cached, k_cur, v_cur, bits: int, correction: 
     mass = np.empty((heads, m), dtype=np.float64)
     quantized = []
     for g in range(kv_heads):
-        kc, ks, kz = quantize(np.asarray(k_cached)[:, g, :], bits, group, rotate, fp8_meta, signs)
+        if key_blocks is None:
+            kc, ks, kz = quantize(np.asarray(k_cached)[:, g, :], bits, group, rotate, fp8_meta, signs)
+        else:
+            assert sum(key_blocks) == np.asarray(k_cached).shape[0]
+            parts, t0 = [], 0
+            for n in key_blocks:
+                c_, s_, z_ = quantize_per_channel(np.asarray(k_cached)[t0:t0 + n, g, :], bits, rotate, signs)
+                parts.append((c_, np.repeat(s_[None, :], n, axis=0), np.repeat(z_[None, :], n, axis=0)))
+                t0 += n
+            kc, ks, kz = (np.concatenate([p_[i] for p_ in parts]) if parts else np.zeros((0, d), dt)
+                          for i, dt in ((0, np.uint8), (1, np.float32), (2, np.float32)))
         vc, vs, vz = quantize(np.asarray(v_cached)[:, g, :], bits, group, rotate, fp8_meta, signs)
         khat, vhat = dequantize(kc, ks, kz), dequantize(vc, vs, vz)
         for h in range(g * ratio, (g + 1) * ratio):

@@ -144,6 +144,67 @@ int kvqo_quantize_rows(int64_t rows, int d, int bits, int group, int rotate,
 }
 
 /*
+ * Per-channel quantization (appendix "Per-Channel Quantization Correction": the
+ * step depends on the channel and is shared by all tokens of the block).  The
+ * same quantizer as kvqo_quantize_rows with the roles of tokens and channels
+ * exchanged: for every channel c of the (optionally rotated) vectors,
+ *
+ *   lo, hi = min, max over the `rows` tokens of the block; a constant channel
+ *            has its range widened to include 0 (all-zero: step 0, codes 0)
+ *   inv    = L / (hi - lo),   z = -rint(lo * inv)
+ *   code   = clamp(rint(u[t][c] * inv) + z, 0, L)      for every token t
+ *   scale[c] = float((hi - lo) / L * n),  zero[c] = float(z)
+ *
+ * x: [rows][d] doubles.  codes: [rows][d] bytes.  scale, zero: [d].
+ */
+int kvqo_quantize_cols(int64_t rows, int d, int bits, int rotate,
+                       const double *x, uint8_t *codes, float *scale, float *zero)
+{
+    if (rows <= 0 || d <= 0) return 1;
+    if (bits < 1 || bits > 8) return 1;
+    if (rotate && !is_pow2(d)) return 1;
+    const double L = (double)((1 << bits) - 1);
+    const double norm = rotate ? inv_sqrt_d(d) : 1.0;
+    double *u = (double *)malloc(sizeof(double) * (size_t)rows * (size_t)d);
+    if (!u) return 1;
+    for (int64_t t = 0; t < rows; ++t) {
+        if (rotate) kvqo_hadamard(d, x + t * d, u + t * d);
+        else memcpy(u + t * d, x + t * d, sizeof(double) * (size_t)d);
+    }
+    for (int c = 0; c < d; ++c) {
+        double lo = u[c], hi = u[c];
+        for (int64_t t = 1; t < rows; ++t) {
+            if (u[t * d + c] < lo) lo = u[t * d + c];
+            if (u[t * d + c] > hi) hi = u[t * d + c];
+        }
+        if (hi == lo) {
+            if (lo > 0.0) lo = 0.0;
+            if (hi < 0.0) hi = 0.0;
+        }
+        if (hi == lo) {
+            for (int64_t t = 0; t < rows; ++t) codes[t * d + c] = 0;
+            scale[c] = 0.0f;
+            zero[c] = 0.0f;
+            continue;
+        }
+        const double range = hi - lo;
+        const double inv = L / range;
+        const double step = range / L;
+        const double z = -rint(lo * inv);
+        for (int64_t t = 0; t < rows; ++t) {
+            double k = rint(u[t * d + c] * inv) + z;
+            if (k < 0.0) k = 0.0;
+            if (k > L) k = L;
+            codes[t * d + c] = (uint8_t)k;
+        }
+        scale[c] = (float)(step * norm);
+        zero[c] = (float)z;
+    }
+    free(u);
+    return 0;
+}
+
+/*
  * FP8 E4M3 (the 8-bit format with 4 exponent bits, bias 7, 3 mantissa bits, no
  * infinities, largest finite value 448, subnormals m * 2^-9): the smallest
  * representable value that is >= x, for x > 0.  Values above 448 saturate at

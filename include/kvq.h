@@ -62,6 +62,16 @@ typedef enum {
                              format of the paper's effective-bitwidth formula B + 24/g */
 } kvq_meta_format;
 
+/* Axis along which the keys share a (scale, zero-point). */
+typedef enum {
+    KVQ_KEYS_PER_TOKEN = 0,  /* one pair (or one per group of channels) per token: the paper's main setting */
+    KVQ_KEYS_PER_CHANNEL = 1 /* one pair per rotated channel, shared by the tokens of one kvq_quantize_append
+                                call (appendix "Per-Channel Quantization Correction").  The correction is then
+                                one scalar per query and appended block.  Values stay per token.  Needs
+                                KVQ_META_FP32 and group_size == head_dim; attention runs on the fp32 vector
+                                kernel.  At most capacity/32 + 2 appended blocks can be live at once */
+} kvq_key_axis;
+
 typedef struct {
     int32_t num_heads;       /* >= 1 */
     int32_t head_dim;        /* 64 or 128 */
@@ -71,6 +81,7 @@ typedef struct {
     int32_t io_dtype;        /* kvq_dtype of q/k/v/out.  KVQ_BF16 with head_dim 128 and group_size == head_dim runs
                                 on the matrix cores; everything else runs an fp32 vector kernel */
     int32_t meta_format;     /* kvq_meta_format */
+    int32_t key_axis;        /* kvq_key_axis */
     int64_t capacity_tokens; /* >= 1; storage is sized for this many tokens per head */
 } kvq_cache_desc;
 
@@ -78,7 +89,10 @@ typedef struct {
  * up to 32 tokens:
  *   KVQ_META_FP32      2 * num_heads * cap32 * (head_dim*bits/8 + 8)
  *   KVQ_META_FP8_BF16  2 * num_heads * cap32 * (head_dim*bits/8 + 3 * head_dim/group_size)
- * (codes plus the metadata, for K and for V).  Returns 0 for an invalid or unsupported description. */
+ * (codes plus the metadata, for K and for V); KVQ_KEYS_PER_CHANNEL adds
+ *   (cap32/32 + 2) * num_heads * head_dim * 8 + cap32 * 4 + num_heads * head_dim * 32, rounded up to 256
+ * (per-block scales and zero-points, the block of every token, work space of the append in flight).
+ * Returns 0 for an invalid or unsupported description. */
 size_t kvq_cache_bytes(const kvq_cache_desc *desc);
 
 /* Creates the host object over caller-provided device storage (`dev_mem`, at least
@@ -216,7 +230,9 @@ kvq_status kvq_attention_diagnostics(const kvq_cache *cache, int64_t cache_start
  * Canonical view of cached tokens [start, start + count), for parity checks and dump/restore.
  * which: 0 = keys, 1 = values.  codes: device uint8 [num_heads][count][head_dim], one code per
  * byte, channel order of the rotated vector.  scales, zeros: device float [num_heads][count][G],
- * G = head_dim / group_size, holding exactly the stored values.  Any of the three output pointers may be NULL.
+ * G = head_dim / group_size, holding exactly the stored values (keys of a KVQ_KEYS_PER_CHANNEL cache:
+ * G = head_dim, every token carries the per-channel values of its block).  Any of the three output
+ * pointers may be NULL.
  */
 kvq_status kvq_cache_export(const kvq_cache *cache, int which, int64_t start, int64_t count,
                             uint8_t *codes, float *scales, float *zeros, void *hip_stream);

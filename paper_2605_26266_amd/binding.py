@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libkvq.so")
 KVQ_OK, KVQ_ERR_INVALID_ARG, KVQ_ERR_UNSUPPORTED, KVQ_ERR_CAPACITY, KVQ_ERR_HIP = range(5)
 KVQ_BF16, KVQ_FP32 = 0, 1
 KVQ_META_FP32, KVQ_META_FP8_BF16 = 0, 1
+KVQ_KEYS_PER_TOKEN, KVQ_KEYS_PER_CHANNEL = 0, 1
 
 # Every symbol declared in include/kvq.h.
 EXPORTED = (
@@ -30,7 +31,7 @@ EXPORTED = (
 class kvq_cache_desc(ctypes.Structure):
     _fields_ = [("num_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("bits", ctypes.c_int32),
                 ("group_size", ctypes.c_int32), ("rotate", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
-                ("meta_format", ctypes.c_int32), ("capacity_tokens", ctypes.c_int64)]
+                ("meta_format", ctypes.c_int32), ("key_axis", ctypes.c_int32), ("capacity_tokens", ctypes.c_int64)]
 
 
 class kvq_attention_opts(ctypes.Structure):
@@ -105,9 +106,10 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 
 def make_desc(num_heads: int, head_dim: int, bits: int, capacity_tokens: int, io_dtype: int = KVQ_BF16,
-              group_size: Optional[int] = None, rotate: int = 1, meta_format: int = KVQ_META_FP32) -> kvq_cache_desc:
+              group_size: Optional[int] = None, rotate: int = 1, meta_format: int = KVQ_META_FP32,
+              key_axis: int = KVQ_KEYS_PER_TOKEN) -> kvq_cache_desc:
     return kvq_cache_desc(num_heads, head_dim, bits, head_dim if group_size is None else group_size, rotate,
-                          io_dtype, meta_format, capacity_tokens)
+                          io_dtype, meta_format, key_axis, capacity_tokens)
 
 
 def kvq_cache_bytes(desc: kvq_cache_desc) -> int:
@@ -292,6 +294,8 @@ def export_all(cache: Cache, which: int, start: int = 0, count: Optional[int] = 
     dev = cache.storage.device
     codes = torch.empty((H, count, d), dtype=torch.uint8, device=dev)
     meta_shape = (H, count) if cache.desc.meta_format == KVQ_META_FP32 else (H, count, d // cache.desc.group_size)
+    if which == 0 and cache.desc.key_axis == KVQ_KEYS_PER_CHANNEL:
+        meta_shape = (H, count, d)   # every token carries the per-channel values of its block
     scales = torch.empty(meta_shape, dtype=torch.float32, device=dev)
     zeros = torch.empty(meta_shape, dtype=torch.float32, device=dev)
     kvq_cache_export(cache, which, start, count, codes, scales, zeros)

@@ -1,8 +1,15 @@
 // Host layer of the C ABI: argument validation, the cache object, dispatch to the kernels.
 // No device memory is allocated here; the cache storage is carved out of the caller's buffer.
+#include <deque>
 #include <new>
 
 #include "kvq_internal.h"
+
+struct kvq_block {
+    int slot;        // index into the per-block metadata arrays
+    int64_t start;   // logical position of the block's first token
+    int64_t count;   // tokens of the block (shrinks when the cache is truncated)
+};
 
 struct kvq_cache {
     kvq_cache_desc desc;
@@ -10,6 +17,21 @@ struct kvq_cache {
     int64_t cap32;  // capacity rounded up to whole tiles
     int64_t base;   // logical position of the oldest live token (the storage is a ring)
     int64_t len;    // live tokens
+    std::deque<kvq_block> blocks;   // KVQ_KEYS_PER_CHANNEL: live appended blocks, oldest first
+    int next_slot;
+
+    // Forget blocks that lie wholly outside [base, base + len).
+    void trim_blocks()
+    {
+        while (!blocks.empty() && blocks.front().start + blocks.front().count <= base) blocks.pop_front();
+        while (!blocks.empty() && blocks.back().start >= base + len) {   // slots stay consecutive: reuse it next
+            next_slot = blocks.back().slot;
+            blocks.pop_back();
+        }
+        if (!blocks.empty() && blocks.back().start + blocks.back().count > base + len)
+            blocks.back().count = base + len - blocks.back().start;
+        if (len == 0) blocks.clear();
+    }
 };
 
 namespace {
@@ -26,11 +48,25 @@ kvq_status check_desc(const kvq_cache_desc *d)
     if (d->group_size > d->head_dim) return KVQ_ERR_UNSUPPORTED;
     if (d->group_size != d->head_dim && d->meta_format != KVQ_META_FP8_BF16) return KVQ_ERR_UNSUPPORTED;
     if (d->rotate != 1) return KVQ_ERR_UNSUPPORTED;
+    if (d->key_axis != KVQ_KEYS_PER_TOKEN && d->key_axis != KVQ_KEYS_PER_CHANNEL) return KVQ_ERR_INVALID_ARG;
+    if (d->key_axis == KVQ_KEYS_PER_CHANNEL && (d->meta_format != KVQ_META_FP32 || d->group_size != d->head_dim))
+        return KVQ_ERR_UNSUPPORTED;
     if (d->capacity_tokens > ((int64_t)1 << 40)) return KVQ_ERR_INVALID_ARG;
     return KVQ_OK;
 }
 
 int64_t round_up_tile(int64_t n) { return (n + kvq::kTileTokens - 1) / kvq::kTileTokens * kvq::kTileTokens; }
+
+int64_t max_blocks_of(int64_t cap32) { return cap32 / kvq::kTileTokens + 2; }
+
+// Bytes of the per-channel key metadata that follow the ordinary storage (0 for per-token keys).
+int64_t channel_bytes(const kvq_cache_desc *d, int64_t cap32)
+{
+    if (d->key_axis != KVQ_KEYS_PER_CHANNEL) return 0;
+    const int64_t hd = (int64_t)d->num_heads * d->head_dim;
+    const int64_t n = max_blocks_of(cap32) * hd * 8 + cap32 * 4 + hd * 32;
+    return (n + 255) / 256 * 256;
+}
 
 size_t elt_bytes(int io_dtype) { return io_dtype == KVQ_BF16 ? 2 : 4; }
 
@@ -55,7 +91,7 @@ size_t kvq_cache_bytes(const kvq_cache_desc *desc)
     const int64_t cap32 = round_up_tile(desc->capacity_tokens);
     const int64_t meta = desc->meta_format == KVQ_META_FP32 ? 8 : 3 * (desc->head_dim / desc->group_size);
     const int64_t per_token = desc->head_dim * desc->bits / 8 + meta;
-    return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token);
+    return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token + channel_bytes(desc, cap32));
 }
 
 kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t bytes, kvq_cache **out)
@@ -72,6 +108,7 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
     c->cap32 = round_up_tile(desc->capacity_tokens);
     c->len = 0;
     c->base = 0;
+    c->next_slot = 0;
     const int64_t H = desc->num_heads;
     const int64_t code_bytes = H * c->cap32 * desc->head_dim * desc->bits / 8;  // multiple of 256
     const int64_t meta_bytes = H * c->cap32 * 4;                                // multiple of 128
@@ -94,7 +131,25 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
         v.k_zero16 = reinterpret_cast<uint16_t *>(p); p += 2 * groups;
         v.v_zero16 = reinterpret_cast<uint16_t *>(p); p += 2 * groups;
         v.k_scale8 = reinterpret_cast<uint8_t *>(p); p += groups;
-        v.v_scale8 = reinterpret_cast<uint8_t *>(p);
+        v.v_scale8 = reinterpret_cast<uint8_t *>(p); p += groups;
+    }
+    v.key_axis = desc->key_axis;
+    v.max_blocks = 0;
+    v.kc_scale = v.kc_zero = nullptr;
+    v.k_block = nullptr;
+    v.kc_range = nullptr;
+    v.kc_inv = v.kc_z = nullptr;
+    if (desc->key_axis == KVQ_KEYS_PER_CHANNEL) {
+        // p stands after the four fp32 arrays of KVQ_META_FP32: a multiple of 128 bytes from a 256-byte base
+        p = static_cast<char *>(dev_mem) + 2 * code_bytes + 4 * meta_bytes;
+        const int64_t hd = H * desc->head_dim;
+        v.max_blocks = (int32_t)max_blocks_of(c->cap32);
+        v.kc_range = reinterpret_cast<unsigned long long *>(p); p += hd * 16;   // 8-byte types first
+        v.kc_inv = reinterpret_cast<double *>(p); p += hd * 8;
+        v.kc_z = reinterpret_cast<double *>(p); p += hd * 8;
+        v.kc_scale = reinterpret_cast<float *>(p); p += (int64_t)v.max_blocks * hd * 4;
+        v.kc_zero = reinterpret_cast<float *>(p); p += (int64_t)v.max_blocks * hd * 4;
+        v.k_block = reinterpret_cast<uint32_t *>(p);
     }
     v.cap_tiles = c->cap32 / kvq::kTileTokens;
     v.num_heads = desc->num_heads;
@@ -115,6 +170,7 @@ kvq_status kvq_cache_reset(kvq_cache *cache)
     if (!cache) return KVQ_ERR_INVALID_ARG;
     cache->len = 0;
     cache->base = 0;
+    cache->blocks.clear();
     return KVQ_OK;
 }
 
@@ -135,6 +191,7 @@ kvq_status kvq_cache_evict(kvq_cache *cache, int64_t n_tokens)
     cache->base += n_tokens;
     cache->len -= n_tokens;
     if (cache->len == 0) cache->base = 0;   // an empty cache starts over at a tile boundary
+    cache->trim_blocks();
     return KVQ_OK;
 }
 
@@ -142,6 +199,7 @@ kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len)
 {
     if (!cache || new_len < 0 || new_len > cache->len) return KVQ_ERR_INVALID_ARG;
     cache->len = new_len;
+    cache->trim_blocks();
     return KVQ_OK;
 }
 
@@ -159,9 +217,18 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
     const int64_t first_tile = cache->base / kvq::kTileTokens;
     const int64_t last_tile = (cache->base + cache->len + n_tokens - 1) / kvq::kTileTokens;
     if (last_tile - first_tile + 1 > cache->view.cap_tiles) return KVQ_ERR_CAPACITY;
+    int slot = 0;
+    if (d.key_axis == KVQ_KEYS_PER_CHANNEL) {
+        if ((int64_t)cache->blocks.size() >= cache->view.max_blocks) return KVQ_ERR_CAPACITY;
+        slot = cache->next_slot;
+    }
     const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->base + cache->len, n_tokens, stride_token,
-                                                     stride_head, static_cast<hipStream_t>(hip_stream));
+                                                     stride_head, slot, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return KVQ_ERR_HIP;
+    if (d.key_axis == KVQ_KEYS_PER_CHANNEL) {
+        cache->blocks.push_back(kvq_block{slot, cache->base + cache->len, n_tokens});
+        cache->next_slot = (slot + 1) % cache->view.max_blocks;
+    }
     cache->len += n_tokens;
     return KVQ_OK;
 }
@@ -227,6 +294,7 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.mass_cached = mass_cached;
     // the exact (sinh) correction is a diagnostic mode: vector kernel only
     force_vector = force_vector || correction == 2;
+    force_vector = force_vector || d.key_axis == KVQ_KEYS_PER_CHANNEL;   // per-channel keys: vector kernel only
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
                              d.group_size == d.head_dim;   // one (scale, zero-point) per token, either format
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);

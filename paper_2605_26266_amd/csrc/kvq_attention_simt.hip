@@ -77,6 +77,34 @@ template <int D, int BITS, typename T> struct SimtRow {
         const int64_t t = t_logical % cap_tokens;   // position in the ring
         const uint32_t *tile = k_head + (t / kTileTokens) * tile_words(D, BITS);
         const int tt = (int)(t % kTileTokens);
+        if (cv.key_axis == KVQ_KEYS_PER_CHANNEL) {
+            // One (scale, zero-point) per channel, shared by the tokens of the key's block (appendix on
+            // per-channel quantization): b = sigma^2/24 sum_c q~_c^2 step_c^2 is the same for every key of
+            // the block; it is summed here next to the dot product, channel by channel.
+            const int64_t slot = cv.k_block[t];
+            const float *sc = cv.kc_scale + (slot * cv.num_heads + head) * D;
+            const float *zc = cv.kc_zero + (slot * cv.num_heads + head) * D;
+            const float cs = a.correction == 1 ? sigma * sigma * (1.0f / 24.0f) : 0.0f;
+            float dot = 0.0f, b = 0.0f;
+            for (int hh = 0; hh < 2; ++hh) {
+                const uint32_t *slot_w = tile + (hh * 32 + tt) * WPL;
+                for (int w = 0; w < WPL; ++w) {
+                    const uint32_t word = slot_w[w];
+                    for (int j = 0; j < 16 / BITS; ++j) {
+                        const int slab = BITS == 2 ? 2 * w + (j >> 2) : w;
+                        const int ch = 16 * slab + 8 * hh + 2 * (j & 3);
+                        for (int e = 0; e < 2; ++e) {
+                            const float code = (float)((word >> (BITS * j + 16 * e)) & MASK);
+                            const float step = sc[ch + e], qs = q_rot[ch + e] * step;
+                            dot = fmaf(qs, code - zc[ch + e], dot);
+                            b = fmaf(cs * qs, qs, b);
+                            if (a.correction == 2) b += log_sinhc(0.5f * sigma * qs);
+                        }
+                    }
+                }
+            }
+            return sigma * dot - b;
+        }
         float scale_g[4], zero_g[4], b = 0.0f;
         for (int g = 0; g < G; ++g) {
             if (fp8_meta) {

@@ -48,6 +48,12 @@ struct CacheView {
     // Randomised Hadamard rotation x -> Hn (s * x): bit c of the mask set means s_c = -1.  All zero is the
     // plain rotation.
     uint32_t sign_mask[4];
+    // KVQ_KEYS_PER_CHANNEL: keys share one (scale, zero-point) per channel within an appended block.
+    int32_t key_axis, max_blocks;
+    float *kc_scale, *kc_zero;       // [max_blocks][H][d]  per block slot
+    uint32_t *k_block;               // [cap32]             block slot of the token at each ring position
+    unsigned long long *kc_range;    // [H][d][2]           work space of the append in flight: min, max (ordered keys)
+    double *kc_inv, *kc_z;           // [H][d]              work space: L / range and the zero-point, per channel
 };
 
 // Sign bits of the channels first .. first + 31 - (first mod 32), bit 0 = channel `first`.
@@ -127,8 +133,9 @@ template <> struct Io<uint16_t> {
 };
 
 // Launchers implemented in the kernel translation units.  All return hipError_t of the launch.
+// block_slot: slot of the block this append creates (KVQ_KEYS_PER_CHANNEL caches only).
 hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
-                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head,
+                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head, int block_slot,
                                   hipStream_t stream);
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream);

@@ -113,14 +113,66 @@ __device__ inline double e4m3_ceil(double x, uint32_t &byte)
     return v;
 }
 
+// Doubles as unsigned keys whose integer order is the numeric order (for atomic min / max).
+__device__ inline unsigned long long order_key(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+__device__ inline double order_value(unsigned long long k)
+{
+    return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
+}
+
+// Per-channel keys, step 0 of an append: empty ranges.
+__global__ void channel_range_init_kernel(CacheView cv)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < cv.num_heads * cv.head_dim) {
+        cv.kc_range[2 * i] = ~0ull;   // minimum so far
+        cv.kc_range[2 * i + 1] = 0ull;   // maximum so far
+    }
+}
+
+// Per-channel keys, step 2 of an append: (scale, zero-point) of every (head, channel) from the range that
+// step 1 left, in the same sequence of double operations as the per-token quantizer; the block's
+// metadata slot and the work space of the quantizing pass are written.
+__global__ void channel_params_kernel(CacheView cv, int block_slot)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= cv.num_heads * cv.head_dim) return;
+    const double L = (double)((1 << cv.bits) - 1);
+    const double norm = cv.head_dim == 64 ? 0.125 : 0.08838834764831845;
+    double lo = order_value(cv.kc_range[2 * i]), hi = order_value(cv.kc_range[2 * i + 1]);
+    if (hi == lo) {
+        lo = lo > 0.0 ? 0.0 : lo;
+        hi = hi < 0.0 ? 0.0 : hi;
+    }
+    const bool degenerate = hi == lo;
+    const double range = hi - lo;
+    const double inv = degenerate ? 0.0 : L / range;
+    const double step = degenerate ? 0.0 : range / L;
+    const double z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
+    cv.kc_inv[i] = inv;
+    cv.kc_z[i] = z;
+    const int64_t slot = (int64_t)block_slot * cv.num_heads * cv.head_dim + i;
+    cv.kc_scale[slot] = (float)(step * norm);
+    cv.kc_zero[slot] = (float)z;
+}
+
 // GROUP == 0: one fp32 (scale, zero-point) per token.  GROUP > 0: one FP8 E4M3 scale and one BF16
 // zero-point per GROUP rotated channels; codes are taken with the stored values.
-template <int D, int BITS, int GROUP, typename T>
+// KMODE (per-channel keys, GROUP == 0 only): 0 = keys per token; 1 = range pass: the keys are rotated and
+// the minimum / maximum of every channel over the appended tokens goes to cv.kc_range, nothing else is
+// written; 2 = the keys take (L / range, zero-point) per channel from cv.kc_inv / cv.kc_z, the values are
+// quantized per token as always, and every token records its block slot.
+template <int D, int BITS, int GROUP, typename T, int KMODE = 0>
 __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, const T *__restrict__ k,
                                                              const T *__restrict__ v, int64_t old_len,
                                                              int64_t n_tokens, int64_t stride_token,
-                                                             int64_t stride_head)
+                                                             int64_t stride_head, int block_slot)
 {
+    static_assert(KMODE == 0 || GROUP == 0, "per-channel keys use fp32 metadata");
     constexpr int EPL = D / 8;            // elements per lane
     constexpr int WPL = D * BITS / 64;    // words per lane slot
     constexpr int L = (1 << BITS) - 1;
@@ -144,7 +196,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
     const double norm = D == 64 ? 0.125 : 0.08838834764831845;  // 1/sqrt(d) rounded to double
 
 #pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < (KMODE == 1 ? 1 : 2); ++pass) {
         double x[EPL];
         if (valid) {
             const T *src = (pass == 0 ? k : v) + (t - old_len) * stride_token + (int64_t)head * stride_head + l8 * EPL;
@@ -179,6 +231,42 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
                 const double other = __shfl_xor(x[i], msk);
                 x[i] = upper ? other - x[i] : x[i] + other;
             }
+        }
+        if constexpr (KMODE == 1) {
+            // Minimum and maximum of every channel over the rows of this tile: across the 8 rows of a
+            // wave by shuffles, across the 4 waves through LDS, then one atomic pair per channel.
+            __shared__ double red[2][4][D];
+            const double inf = __longlong_as_double(0x7ff0000000000000ll);
+            const int wv = threadIdx.x >> 6, ln = threadIdx.x & 63;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) {
+                double lo_i = valid ? x[i] : inf, hi_i = valid ? x[i] : -inf;
+#pragma unroll
+                for (int msk = 8; msk < 64; msk <<= 1) {
+                    const double ol = __shfl_xor(lo_i, msk), oh = __shfl_xor(hi_i, msk);
+                    lo_i = ol < lo_i ? ol : lo_i;
+                    hi_i = oh > hi_i ? oh : hi_i;
+                }
+                if (ln < 8) {
+                    red[0][wv][ln * EPL + i] = lo_i;
+                    red[1][wv][ln * EPL + i] = hi_i;
+                }
+            }
+            __syncthreads();
+            if (threadIdx.x < D) {
+                double lo_c = red[0][0][threadIdx.x], hi_c = red[1][0][threadIdx.x];
+#pragma unroll
+                for (int w2 = 1; w2 < 4; ++w2) {
+                    lo_c = red[0][w2][threadIdx.x] < lo_c ? red[0][w2][threadIdx.x] : lo_c;
+                    hi_c = red[1][w2][threadIdx.x] > hi_c ? red[1][w2][threadIdx.x] : hi_c;
+                }
+                unsigned long long *r = cv.kc_range + 2 * ((int64_t)head * D + threadIdx.x);
+                if (lo_c <= hi_c) {   // the tile holds at least one appended token
+                    atomicMin(r, order_key(lo_c));
+                    atomicMax(r + 1, order_key(hi_c));
+                }
+            }
+            return;
         }
         double lo = x[0], hi = x[0];
 #pragma unroll
@@ -222,7 +310,12 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
         int code[EPL];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-            double c = __builtin_rint(x[i] * inv) + z;
+            double inv_i = inv, z_i = z;
+            if (KMODE == 2 && pass == 0) {   // per-channel keys: this lane's channels are EPL * l8 + i
+                inv_i = cv.kc_inv[head * D + l8 * EPL + i];
+                z_i = cv.kc_z[head * D + l8 * EPL + i];
+            }
+            double c = __builtin_rint(x[i] * inv_i) + z_i;
             c = c < 0.0 ? 0.0 : c;
             c = c > (double)L ? (double)L : c;
             code[i] = (int)c;
@@ -264,7 +357,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
                     const int hh = l8 & 1;
                     if (BITS == 4 || (l8 & 2) == 0) k_tile[(hh * 32 + row) * WPL + q] = mine[0];
                 }
-                if constexpr (GROUP == 0) {
+                if constexpr (KMODE == 2) {
+                    if (l8 == 2 && head == 0 && valid) cv.k_block[ptile * kTileTokens + row] = (uint32_t)block_slot;
+                } else if constexpr (GROUP == 0) {
                     if (l8 == 2) cv.k_scale[meta_idx] = scale;
                     if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
                 } else if (group_writer) {
@@ -534,7 +629,12 @@ __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int6
         else value_code_pos(D, BITS, tt, c, word, shift);
         if (codes) codes[((int64_t)head * count + i) * D + c] = (uint8_t)((base[word] >> shift) & ((1u << BITS) - 1u));
         const int64_t mi = ((int64_t)head * cv.cap_tiles + tile) * kTileTokens + tt;
-        if (cv.meta_format == KVQ_META_FP32) {
+        if (cv.key_axis == KVQ_KEYS_PER_CHANNEL && which == 0) {   // every token carries its block's per-channel values
+            const int64_t slot = cv.k_block[tile * kTileTokens + tt];
+            const int64_t si = (slot * cv.num_heads + head) * D + c, oi = ((int64_t)head * count + i) * D + c;
+            if (scales) scales[oi] = cv.kc_scale[si];
+            if (zeros) zeros[oi] = cv.kc_zero[si];
+        } else if (cv.meta_format == KVQ_META_FP32) {
             if (c == 0) {
                 if (scales) scales[(int64_t)head * count + i] = which == 0 ? cv.k_scale[mi] : cv.v_scale[mi];
                 if (zeros)
@@ -552,25 +652,36 @@ __global__ __launch_bounds__(D) void export_kernel(CacheView cv, int which, int6
 
 template <int D, int BITS, typename T>
 hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t old_len, int64_t n, int64_t st,
-                    int64_t sh, hipStream_t stream)
+                    int64_t sh, int block_slot, hipStream_t stream)
 {
     const int64_t first_tile = old_len / kTileTokens;
     const int64_t last_tile = (old_len + n - 1) / kTileTokens;
     const dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)cv.num_heads);
     const T *kp = static_cast<const T *>(k), *vp = static_cast<const T *>(v);
+    if (cv.key_axis == KVQ_KEYS_PER_CHANNEL) {
+        // ranges of the block -> per-channel parameters -> codes (keys per channel, values per token)
+        const unsigned nb = (unsigned)((cv.num_heads * cv.head_dim + 255) / 256);
+        hipLaunchKernelGGL(channel_range_init_kernel, dim3(nb), dim3(256), 0, stream, cv);
+        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T, 1>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n,
+                           st, sh, block_slot);
+        hipLaunchKernelGGL(channel_params_kernel, dim3(nb), dim3(256), 0, stream, cv, block_slot);
+        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T, 2>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n,
+                           st, sh, block_slot);
+        return hipGetLastError();
+    }
     if (cv.meta_format == KVQ_META_FP8_BF16) {
         if (cv.group_size == 32)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 32, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 32, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
         else if (cv.group_size == 64)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 64, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 64, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
         else if constexpr (D == 128)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 128, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 128, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
         else
             return hipErrorInvalidValue;
     } else if constexpr (D == 128) {
         hipLaunchKernelGGL((quantize_append_kernel128<BITS, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
     } else {
-        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
     }
     return hipGetLastError();
 }
@@ -578,14 +689,14 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
 }  // namespace
 
 hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
-                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head,
+                                  int64_t n_tokens, int64_t stride_token, int64_t stride_head, int block_slot,
                                   hipStream_t stream)
 {
     const bool bf16 = cv.io_dtype == KVQ_BF16;
-#define KVQ_Q(D, B)                                                                                             \
-    if (cv.head_dim == D && cv.bits == B)                                                                       \
-        return bf16 ? launch_q<D, B, uint16_t>(cv, k, v, old_len, n_tokens, stride_token, stride_head, stream)  \
-                    : launch_q<D, B, float>(cv, k, v, old_len, n_tokens, stride_token, stride_head, stream);
+#define KVQ_Q(D, B)                                                                                                         \
+    if (cv.head_dim == D && cv.bits == B)                                                                                   \
+        return bf16 ? launch_q<D, B, uint16_t>(cv, k, v, old_len, n_tokens, stride_token, stride_head, block_slot, stream)  \
+                    : launch_q<D, B, float>(cv, k, v, old_len, n_tokens, stride_token, stride_head, block_slot, stream);
     KVQ_Q(128, 2)
     KVQ_Q(128, 4)
     KVQ_Q(64, 2)

@@ -30,9 +30,11 @@ def _dev(x: np.ndarray, io_dtype: str, device: str) -> torch.Tensor:
 
 
 def run(workload: str = "small", rows: int = 256, heads: Optional[int] = None, cached_chunks: Optional[int] = None,
-        settings=((2, None), (2, 32), (4, None), (4, 32)), corrections=(0, 1), device: str = "cuda:0") -> List[Dict]:
-    """settings: (bits, group) pairs; group None = one fp32 (scale, zero-point) per token, else FP8/BF16
-    metadata per group of that many rotated channels.  Returns one record per (setting, correction)."""
+        settings=((2, None), (2, 32), (2, "channel"), (4, None), (4, 32), (4, "channel")), corrections=(0, 1),
+        device: str = "cuda:0") -> List[Dict]:
+    """settings: (bits, group) pairs; group None = one fp32 (scale, zero-point) per token, an integer = FP8/BF16
+    metadata per group of that many rotated channels, "channel" = keys quantized per channel over each cached
+    chunk (values per token).  Returns one record per (setting, correction)."""
     base = wl.WORKLOADS[workload]
     n_heads = base.num_heads if heads is None else min(heads, base.num_heads)
     n_chunks = base.cached_chunks if cached_chunks is None else cached_chunks
@@ -46,11 +48,16 @@ def run(workload: str = "small", rows: int = 256, heads: Optional[int] = None, c
     q = _dev(wl.chunk_q(replace(base, cached_chunks=n_chunks), heads=head_ids, rows=row_ids), io, device)
     records = []
     for bits, group in settings:
+        per_channel = group == "channel"
+        group = None if per_channel else group
         meta = B.KVQ_META_FP32 if group is None else B.KVQ_META_FP8_BF16
         cache = B.Cache(B.make_desc(n_heads, base.head_dim, bits, k_ref.shape[0],
-                                    B.KVQ_BF16 if io == "bf16" else B.KVQ_FP32, group_size=group, meta_format=meta),
+                                    B.KVQ_BF16 if io == "bf16" else B.KVQ_FP32, group_size=group, meta_format=meta,
+                                    key_axis=B.KVQ_KEYS_PER_CHANNEL if per_channel else B.KVQ_KEYS_PER_TOKEN),
                         device)
-        B.kvq_quantize_append(cache, k_ref, v_ref)
+        n_chunk = base.chunk_tokens
+        for c in range(n_chunks):      # one append per cached chunk, as a generation loop would do
+            B.kvq_quantize_append(cache, k_ref[c * n_chunk:(c + 1) * n_chunk], v_ref[c * n_chunk:(c + 1) * n_chunk])
         for correction in corrections:
             diag = torch.empty((n_heads, q.shape[0], 4), dtype=torch.float32, device=device)
             B.kvq_attention_diagnostics(cache, 0, len(cache), q, k_ref, v_ref, k_cur, v_cur, diag, correction=correction)
@@ -58,7 +65,8 @@ def run(workload: str = "small", rows: int = 256, heads: Optional[int] = None, c
             d = diag.double().cpu().numpy().reshape(-1, 4)
             steal = d[:, 1] - d[:, 0]
             records.append({"workload": workload, "bits": bits, "group": group or base.head_dim,
-                            "metadata": "fp32" if group is None else "fp8/bf16", "correction": correction,
+                            "metadata": "per-chan" if per_channel else "fp32" if group is None else "fp8/bf16",
+                            "correction": correction,
                             "rows": int(d.shape[0]), "cached_tokens": int(k_ref.shape[0]),
                             "current_tokens": int(k_cur.shape[0]),
                             "mean_P_S": float(d[:, 0].mean()), "mean_stealing": float(steal.mean()),

@@ -25,11 +25,13 @@ def to_dev(x: np.ndarray, io_dtype: str) -> torch.Tensor:
     return t.to(torch.bfloat16) if io_dtype == "bf16" else t
 
 
-def make_cache(w: wl.Workload, capacity: int, heads: int = None, group: int = None, fp8_meta: bool = False) -> B.Cache:
+def make_cache(w: wl.Workload, capacity: int, heads: int = None, group: int = None, fp8_meta: bool = False,
+               per_channel_keys: bool = False) -> B.Cache:
     io = B.KVQ_BF16 if w.io_dtype == "bf16" else B.KVQ_FP32
     meta = B.KVQ_META_FP8_BF16 if fp8_meta else B.KVQ_META_FP32
+    axis = B.KVQ_KEYS_PER_CHANNEL if per_channel_keys else B.KVQ_KEYS_PER_TOKEN
     return B.Cache(B.make_desc(w.num_heads if heads is None else heads, w.head_dim, w.bits, capacity, io,
-                               group_size=group, meta_format=meta), DEV)
+                               group_size=group, meta_format=meta, key_axis=axis), DEV)
 
 
 def export_np(cache: B.Cache, which: int, start: int = 0, count: int = None):

@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         constexpr int kCodeIters = 2 * kCodeVecs / kThreads;        // vectors per thread (keys, then values)
         u32x4 pre_kv[kCodeIters];
         float pre_a = 0.0f, pre_b = 0.0f, pre_c = 0.0f;
-        bool pre_valid = false;
+        uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1; // one (key, operand half) per thread below 256
         const bool ld_meta = tid < 2 * kStageKeys;
         auto prefetch = [&](int stage) {
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             if (!ld_meta) return;
             int64_t tok = tile0 * kTileTokens + ld_key;
-            pre_valid = tok >= cs && tok < ce;
+            pre_in_window = (tok >= cs && tok < ce) ? 1u : 0u;
             tok = phys_tile0 * kTileTokens + ld_key;
             tok = tok >= cap_tokens ? tok - cap_tokens : tok;
             tok = tok >= cap_tokens ? tok - cap_tokens : tok;
@@ -392,13 +392,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         };
         auto commit = [&](int stage) {
             if (stage >= n_stages) return;
-            uint32_t *buf = lds + (stage % kBuffers) * St::kWords;
+            uint32_t *buf = lds + ((uint32_t)stage % kBuffers) * St::kWords;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
                 const int g = tid + kThreads * it;   // kV == kK + 4 * kCodeVecs: keys then values, contiguous
                 *reinterpret_cast<u32x4 *>(buf + St::kK + 4 * g) = pre_kv[it];
             }
             if (!ld_meta) return;
+            const bool pre_valid = pre_in_window != 0u;
             // Position of this key in the per-lane order of the score tile: [tile][hh][4 g + r].
             const int tl = ld_key >> 5, r = ld_key & 31;
             const int slot = tl * 32 + ((r >> 2) & 1) * 16 + 4 * (r >> 3) + (r & 3);
@@ -440,7 +441,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // ---- pieces of one pipeline iteration
         // Scores of tile t (raw accumulators): constant-term MFMA, then high and low query parts.
         auto score_tile = [&](int t, f32x16 (&sn)[kRB]) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int tl = t & 3;
             uint32_t kw[WPL];
             {
@@ -485,7 +486,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         };
         // e = scale_i * raw - reference; returns the tile maximum of e per row block.
         auto finalize_tile = [&](int t, const f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB]) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const float *ks = reinterpret_cast<const float *>(buf + St::kKScale) + (t & 3) * 32 + hh * 16;
             float k_scale[16];
 #pragma unroll
@@ -505,7 +506,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         };
         // p = 2^e, partial sums, p' = p * value-scale rounded to bf16 (B operands), tau.
         auto exp_tile = [&](int t, const float (&e)[kRB][16], u32x4 (&pop)[kRB][2]) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int pos = (t & 3) * 32 + hh * 16;
             const float *vsp = reinterpret_cast<const float *>(buf + St::kVScale) + pos;
             float v_scale[16];
@@ -544,7 +545,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         };
         // O^T += V^T P^T on raw codes.
         auto pv_tile = [&](int t, const u32x4 (&pop)[kRB][2]) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             uint32_t vw[WPL];
             {
                 const uint32_t *src = buf + St::kV + (t & 3) * 64 * WPL + lane * WPL;
@@ -574,7 +575,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             u32x4 cop;          // its constant-term operand
         };
         auto prefetch_keys = [&](int t, Prefetched &pf) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int tl = t & 3;
             const uint32_t *src = buf + St::kK + tl * 64 * WPL + lane * WPL;
 #pragma unroll
@@ -586,8 +587,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         };
         auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
                                    u32x4 (&pop)[kRB][2], uint32_t &lo_flag) {
-            const uint32_t *bufn = lds + (((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
-            const uint32_t *bufc = lds + ((t >> 2) % kBuffers) * St::kWords;         // holds tile t
+            const uint32_t *bufn = lds + ((uint32_t)((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
+            const uint32_t *bufc = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;         // holds tile t
             const int tln = (t + 1) & 3, tlc = t & 3;
             const int pos = tlc * 32 + hh * 16;
             // requests for this iteration's exponential work
@@ -724,7 +725,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // flags the stages that hold one; the fast loop only carries the flag and is left after such a tile,
         // whose probabilities (still in pop) then meet the low parts here.
         auto add_low_zero_points = [&](int t, const u32x4 (&pop)[kRB][2]) {
-            const uint32_t *buf = lds + ((t >> 2) % kBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int pos = (t & 3) * 32 + hh * 16;
             const u32x4 l0 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2);
             const u32x4 l1 = *reinterpret_cast<const u32x4 *>(buf + St::kVzLo + pos / 2 + 4);
@@ -756,6 +757,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         Prefetched pf;
         prefetch_keys(1, pf);
         int t = 0;
+        int t_open = 6;      // stage s (tiles 4 s ..) is opened while tile 4 s - 2 is being scored: s = 2 at t = 6
         bool done = false;
         uint32_t lo_flag = 0u;   // nonzero: tile t-1 still owes tau its low zero-point parts
         while (!done) {
@@ -772,7 +774,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     done = true;
                     break;
                 }
-                if (((t + 2) & 3) == 0 && t + 2 >= 8) open_stage((t + 2) >> 2);
+                if (t == t_open) {
+                    open_stage((t + 2) >> 2);
+                    t_open += 4;
+                }
                 fused_iteration(t, pf, sn, e, tmax, pop, lo_flag);
                 ++t;
                 if (__any(over_threshold(tmax) || lo_flag != 0u)) break;

@@ -346,7 +346,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         u32x4 pre_kv[kCodeIters];
         uint8_t pre_ks[G], pre_vs[G];      // E4M3 encodings
         uint16_t pre_kz[G], pre_vz[G];     // BF16 encodings
-        bool pre_valid = false;
+        uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1;
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 pre_kv[it] = *reinterpret_cast<const u32x4 *>((g < kCodeVecs ? cv.k_codes : cv.v_codes) + word);
             }
             int64_t tok = tile0 * kTileTokens + ld_key;
-            pre_valid = tok >= cs && tok < ce;
+            pre_in_window = (tok >= cs && tok < ce) ? 1u : 0u;
             tok = phys_tile0 * kTileTokens + ld_key;
             tok = tok >= cap_tokens ? tok - cap_tokens : tok;
             tok = tok >= cap_tokens ? tok - cap_tokens : tok;
@@ -384,12 +384,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         };
         auto commit = [&](int stage) {
             if (stage >= n_stages) return;
-            uint32_t *buf = lds + (stage % kGBuffers) * St::kWords;
+            uint32_t *buf = lds + ((uint32_t)stage % kGBuffers) * St::kWords;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
                 const int g = tid + kThreads * it;
                 *reinterpret_cast<u32x4 *>(buf + St::kK + 4 * g) = pre_kv[it];
             }
+            const bool pre_valid = pre_in_window != 0u;
             const int tl = ld_key >> 5, r = ld_key & 31;
             // Keys outside the window: every key-side factor is 0, the mask slot carries the bias.
             KeyGroup kg[G];
@@ -456,7 +457,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             u32x4 cop[NC];
         };
         auto prefetch_keys = [&](int t, Prefetched &pf) {
-            const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             const int tl = t & 3;
             const uint32_t *src = buf + St::kK + tl * 64 * WPL + lane * WPL;
 #pragma unroll
@@ -470,7 +471,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         };
         // Steps of the lane's key for tile t, one f16 pair per group.
         auto load_key_steps = [&](int t, uint32_t (&ks)[G]) {
-            const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             const uint32_t *src = buf + St::kKs + ((t & 3) * 32 + n) * G;
             if constexpr (G == 4) {
                 const u32x4 w = *reinterpret_cast<const u32x4 *>(src);
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         };
         // tau of tile t from its probabilities: rows 4 hh .. 4 hh + 3 of the result belong to this lane half.
         auto load_tau_operand = [&](int t, u32x4 (&top)[2]) {
-            const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             const uint32_t *src = buf + St::kTau + ((((t & 3) * 2) * 2 + hh) * 8 + (n & 7)) * 4;
             top[0] = *reinterpret_cast<const u32x4 *>(src);
             top[1] = *reinterpret_cast<const u32x4 *>(src + 2 * 8 * 4);
@@ -591,7 +592,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             }
         };
         auto load_value_words = [&](int t, uint32_t (&vw)[WPL]) {
-            const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             const uint32_t *src = buf + St::kV + (t & 3) * 64 * WPL + lane * WPL;
 #pragma unroll
             for (int i = 0; i < WPL / 4; ++i) {
@@ -601,7 +602,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         };
         // O^T += V^T P^T with the steps folded into the value operand; tau from the same probabilities.
         auto pv_tile = [&](int t, const u32x4 (&pop)[kRB][2]) {
-            const uint32_t *buf = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             uint32_t vw[WPL];
             load_value_words(t, vw);
             static_for<4>([&](auto b_) {
@@ -623,7 +624,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         // P*V MFMAs of tile t next to the reference subtraction of tile t+1, then tau of tile t.
         auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
                                    u32x4 (&pop)[kRB][2]) {
-            const uint32_t *bufc = lds + ((t >> 2) % kGBuffers) * St::kWords;
+            const uint32_t *bufc = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             uint32_t ks[G];
             load_key_steps(t + 1, ks);
             uint32_t off = lo_off;
@@ -727,6 +728,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         Prefetched pf;
         prefetch_keys(1, pf);
         int t = 0;
+        int t_open = 6;      // stage s (tiles 4 s ..) is opened while tile 4 s - 2 is being scored: s = 2 at t = 6
         bool done = false;
         while (!done) {
             move_reference(e, tmax);
@@ -737,7 +739,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                     done = true;
                     break;
                 }
-                if (((t + 2) & 3) == 0 && t + 2 >= 8) open_stage((t + 2) >> 2);
+                if (t == t_open) {
+                    open_stage((t + 2) >> 2);
+                    t_open += 4;
+                }
                 fused_iteration(t, pf, sn, e, tmax, pop);
                 ++t;
                 if (__any(over_threshold(tmax))) break;

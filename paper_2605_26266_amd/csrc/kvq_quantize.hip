@@ -420,7 +420,10 @@ __device__ inline uint32_t quad_or(uint32_t v)
     return v;
 }
 
-template <int BITS, typename T>
+// GROUP as in the generic kernel: 0 = one fp32 pair per token, 32 / 64 / 128 = FP8 E4M3 scale and BF16
+// zero-point per GROUP rotated channels.  After the exchange a lane holds two channels of every slab, so a
+// group of 32 (64, 128) channels is registers 4 g .. 4 g + 3 (8 g .. 8 g + 7, all) of all eight lanes.
+template <int BITS, typename T, int GROUP = 0>
 __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, const T *__restrict__ k,
                                                                 const T *__restrict__ v, int64_t old_len,
                                                                 int64_t n_tokens, int64_t stride_token,
@@ -507,37 +510,70 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
                 }
         }
         // No NaNs can occur here (finite inputs, exact sums), so min/max are plain selections.
-        double lo = __builtin_fmin(x[0], x[1]), hi = __builtin_fmax(x[0], x[1]);
-#pragma unroll
-        for (int i = 2; i < 16; ++i) {
-            lo = __builtin_fmin(lo, x[i]);
-            hi = __builtin_fmax(hi, x[i]);
-        }
-#pragma unroll
-        for (int msk = 1; msk < 8; msk <<= 1) {
-            lo = __builtin_fmin(lo, __shfl_xor(lo, msk));
-            hi = __builtin_fmax(hi, __shfl_xor(hi, msk));
-        }
-        if (hi == lo) {  // constant vector: widen the range to include 0
-            lo = lo > 0.0 ? 0.0 : lo;
-            hi = hi < 0.0 ? 0.0 : hi;
-        }
-        const bool degenerate = hi == lo;  // all-zero vector
-        const double range = hi - lo;
-        const double inv = degenerate ? 0.0 : (double)L / range;
-        const double step = degenerate ? 0.0 : range / (double)L;
-        const double z = degenerate ? 0.0 : -__builtin_rint(lo * inv);
-        // round(u * inv) + z and the clamp are exact in 32-bit integers (|z| + L < 2^31 by the documented
-        // domain), so they give the same codes as the double-precision statement of Eq. 1.
-        const int zi = (int)z;
+        constexpr int kG = GROUP == 0 ? 1 : D / GROUP;   // groups per vector
+        constexpr int kRegs = 16 / kG;                    // registers of a lane that belong to one group
         uint32_t code[16];
+        // Range of every group (all eight lanes end up with all of them); lane l then works out the
+        // parameters of group l mod kG only and the lanes exchange the results.
+        double lo_mine = 0.0, hi_mine = 0.0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int c = (int)__builtin_rint(x[i] * inv) + zi;
-            code[i] = (uint32_t)(c < 0 ? 0 : (c > L ? L : c));   // one v_med3_i32
+        for (int g = 0; g < kG; ++g) {
+            double lo = __builtin_fmin(x[kRegs * g], x[kRegs * g + 1]), hi = __builtin_fmax(x[kRegs * g], x[kRegs * g + 1]);
+#pragma unroll
+            for (int i = 2; i < kRegs; ++i) {
+                lo = __builtin_fmin(lo, x[kRegs * g + i]);
+                hi = __builtin_fmax(hi, x[kRegs * g + i]);
+            }
+#pragma unroll
+            for (int msk = 1; msk < 8; msk <<= 1) {
+                lo = __builtin_fmin(lo, __shfl_xor(lo, msk));
+                hi = __builtin_fmax(hi, __shfl_xor(hi, msk));
+            }
+            if (g == 0 || (l8 & (kG - 1)) == g) { lo_mine = lo; hi_mine = hi; }
         }
-        const float scale = (float)(step * 0.08838834764831845);  // 1/sqrt(128) rounded to double
-        const float zero = (float)z;
+        double inv_mine, z_mine;
+        float my_scale, my_zero;
+        uint32_t my_byte = 0u;
+        {
+            double lo = lo_mine, hi = hi_mine;
+            if (hi == lo) {  // constant vector (group): widen the range to include 0
+                lo = lo > 0.0 ? 0.0 : lo;
+                hi = hi < 0.0 ? 0.0 : hi;
+            }
+            const bool degenerate = hi == lo;  // all-zero vector (group)
+            const double range = hi - lo;
+            if constexpr (GROUP == 0) {
+                inv_mine = degenerate ? 0.0 : (double)L / range;
+                const double step = degenerate ? 0.0 : range / (double)L;
+                z_mine = degenerate ? 0.0 : -__builtin_rint(lo * inv_mine);
+                my_scale = (float)(step * 0.08838834764831845);  // 1/sqrt(128) rounded to double
+                my_zero = (float)z_mine;
+            } else {
+                // step in the normalised domain, rounded up to the format; everything after uses the stored values
+                const double step = range / (double)L * 0.08838834764831845;
+                const double s8 = degenerate ? 0.0 : e4m3_ceil(step, my_byte);
+                inv_mine = degenerate ? 0.0 : 0.08838834764831845 / s8;
+                const double zr = degenerate ? 0.0 : -__builtin_rint(lo * inv_mine);
+                my_zero = bf16_to_float(float_to_bf16((float)zr));
+                z_mine = (double)my_zero;
+                my_scale = (float)s8;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < kG; ++g) {
+            // lanes g, g + kG, ... of the vector hold group g's parameters; take them from lane g
+            const double inv = kG == 1 ? inv_mine : __shfl(inv_mine, g, 8);
+            const int zi = kG == 1 ? (int)z_mine : __shfl((int)z_mine, g, 8);
+            // round(u * inv) + z and the clamp are exact in 32-bit integers (|z| + L < 2^31 by the documented
+            // domain), so they give the same codes as the double-precision statement of Eq. 1.
+#pragma unroll
+            for (int i = kRegs * g; i < kRegs * (g + 1); ++i) {
+                const int c = (int)__builtin_rint(x[i] * inv) + zi;
+                code[i] = (uint32_t)(c < 0 ? 0 : (c > L ? L : c));   // one v_med3_i32
+            }
+        }
+        const float scale = my_scale, zero = my_zero;   // GROUP == 0: the same in every lane
+        const int64_t group_idx = meta_idx * kG + l8;   // KVQ_META_FP8_BF16: lane g < kG stores group g's pair
 
         if (pass == 0) {
             // register index 2 j + e <-> slab j, element pair position `reg`, half `hh`
@@ -565,16 +601,26 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
                 }
             }
             if (valid || tail) {
-                if (l8 == 2) cv.k_scale[meta_idx] = scale;
-                if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                if constexpr (GROUP == 0) {
+                    if (l8 == 2) cv.k_scale[meta_idx] = scale;
+                    if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                } else if (l8 < kG) {
+                    cv.k_scale8[group_idx] = (uint8_t)my_byte;
+                    cv.k_zero16[group_idx] = float_to_bf16(my_zero);
+                }
             }
         } else {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 *reinterpret_cast<uint16_t *>(&v_stage[row][16 * j + 2 * l8]) = (uint16_t)(code[2 * j] | (code[2 * j + 1] << 8));
             if (valid || tail) {
-                if (l8 == 2) cv.v_scale[meta_idx] = scale;
-                if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                if constexpr (GROUP == 0) {
+                    if (l8 == 2) cv.v_scale[meta_idx] = scale;
+                    if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                } else if (l8 < kG) {
+                    cv.v_scale8[group_idx] = (uint8_t)my_byte;
+                    cv.v_zero16[group_idx] = float_to_bf16(my_zero);
+                }
             }
         }
     }
@@ -668,6 +714,17 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
         hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T, 2>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n,
                            st, sh, block_slot);
         return hipGetLastError();
+    }
+    if constexpr (D == 128) {
+        if (cv.meta_format == KVQ_META_FP8_BF16) {
+            if (cv.group_size == 32)
+                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 32>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            else if (cv.group_size == 64)
+                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 64>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            else
+                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 128>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+            return hipGetLastError();
+        }
     }
     if (cv.meta_format == KVQ_META_FP8_BF16) {
         if (cv.group_size == 32)

@@ -882,18 +882,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 }
             }
         };
+        // The key rows of a tile go straight from global memory into A operands; they are requested one
+        // tile ahead so that their latency is covered by the tile in between.
+        u32x4 kop[8];
+        auto prefetch_k = [&](int tile) {
+            int64_t key = (int64_t)tile * kTileTokens + n;
+            key = key < a.n_cur ? key : a.n_cur - 1;
+            const uint16_t *src = k_base + key * a.stride_token + 8 * hh;
+#pragma unroll
+            for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 16 * slab);
+        };
         auto score_cur = [&](int tile, float (&e)[kRB][16], float (&tmax)[kRB]) {
             f32x16 s[kRB];
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[rb][v] = 0.0f;
-            int64_t key = (int64_t)tile * kTileTokens + n;
-            key = key < a.n_cur ? key : a.n_cur - 1;
-            const uint16_t *src = k_base + key * a.stride_token + 8 * hh;
-            u32x4 kop[8];
-#pragma unroll
-            for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 16 * slab);
 #pragma unroll
             for (int slab = 0; slab < 8; ++slab) {
 #pragma unroll
@@ -958,24 +962,109 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
         };
 
+        // One pipeline iteration: the score MFMAs of tile + 1 are interleaved with the exponentials of
+        // `tile`, the P*V MFMAs of `tile` with the scaling and masking of tile + 1 (same pattern as the
+        // cached-key loop, without unpacking).  On entry e holds tile's scores minus the reference, kop
+        // the key rows of tile + 1; on exit e and tmax describe tile + 1.
+        auto fused_cur = [&](int tile, float (&e)[kRB][16], float (&tmax)[kRB]) {
+            f32x16 s[kRB];
+            float lsum[kRB] = {};
+            uint32_t pw[kRB][8];
+            auto exp_chunk = [&](auto c_) {
+                constexpr int C = decltype(c_)::value;
+                constexpr int RB = (C * kRB) / 8, I0 = (C * kRB) % 8;
+#pragma unroll
+                for (int i = I0; i < I0 + kRB; ++i) {
+                    const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
+                    const float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
+                    lsum[RB] += p0 + p1;
+                    pw[RB][i] = pack_bf16(p0, p1);
+                }
+            };
+            f32x16 zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+            KVQ_CHUNK_FENCE();
+            static_for<8>([&](auto s_) {
+                constexpr int SLAB = decltype(s_)::value;
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) s[rb] = mfma_bf16(kop[SLAB], qop[rb][SLAB], SLAB == 0 ? zero : s[rb]);
+                exp_chunk(IntC<SLAB>{});
+                KVQ_CHUNK_FENCE();
+            });
+            u32x4 pop[kRB][2];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) {
+                l_r[rb] += lsum[rb];
+                pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
+                pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
+            }
+            if (tile + 2 < n_tiles) prefetch_k(tile + 2);   // the score MFMAs have consumed kop
+            KVQ_CHUNK_FENCE();
+            const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(vt(tile));
+            const int64_t key_base = (int64_t)(tile + 1) * kTileTokens + 4 * hh;
+            const bool edge = a.causal != 0 || (int64_t)(tile + 2) * kTileTokens > a.n_cur;
+            int64_t visible[kRB];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) {
+                visible[rb] = a.n_cur;
+                if (a.causal) {
+                    const int64_t upto = wave_row0 + 32 * rb + n + (a.n_cur - a.m) + 1;
+                    visible[rb] = upto < visible[rb] ? upto : visible[rb];
+                }
+            }
+            float mx[kRB];
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
+            static_for<4>([&](auto b_) {
+                constexpr int B = decltype(b_)::value;
+                const uint32_t *rowp = vsrc + (32 * B + n) * kVtRowWords + 2 * hh;
+#pragma unroll
+                for (int sl = 0; sl < 2; ++sl) {
+                    const u32x2 lo = *reinterpret_cast<const u32x2 *>(rowp + 8 * sl);
+                    const u32x2 hi = *reinterpret_cast<const u32x2 *>(rowp + 8 * sl + 4);
+                    u32x4 vop;
+                    vop.x = lo.x; vop.y = lo.y; vop.z = hi.x; vop.w = hi.y;
+#pragma unroll
+                    for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(vop, pop[rb][sl], o[B][rb]);
+                }
+                constexpr int RB = (B * 4 * kRB) / 16, V0 = (B * 4 * kRB) % 16;   // one quarter of the next tile
+#pragma unroll
+                for (int v = V0; v < V0 + 4 * kRB; ++v) {
+                    float x = fmaf(s[RB][v], c_log, -m_ref[RB]);
+                    if (edge) x = key_base + 8 * (v >> 2) + (v & 3) < visible[RB] ? x : kMaskBias;
+                    e[RB][v] = x;
+                }
+#pragma unroll
+                for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
+                KVQ_CHUNK_FENCE();
+            });
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(mx[rb]);
+        };
+
         prefetch_v(0);
+        prefetch_k(0);
         commit_v(vt(0));
         __syncthreads();
         float e[kRB][16], tmax[kRB];
         int tile = 0;
         score_cur(0, e, tmax);
+        if (n_tiles > 1) prefetch_k(1);
         bool done = false;
         while (!done) {
             move_reference(e, tmax);
             for (;;) {
-                const bool more = tile + 1 < n_tiles;
-                if (more) prefetch_v(tile + 1);
-                pv_cur(tile, e);
-                if (more) commit_v(vt(tile + 1));
+                if (tile + 1 >= n_tiles) {
+                    pv_cur(tile, e);
+                    done = true;
+                    break;
+                }
+                prefetch_v(tile + 1);
+                fused_cur(tile, e, tmax);
+                commit_v(vt(tile + 1));
                 __syncthreads();
-                if (!more) { done = true; break; }
                 ++tile;
-                score_cur(tile, e, tmax);
                 if (__any(over_threshold(tmax))) break;
             }
         }

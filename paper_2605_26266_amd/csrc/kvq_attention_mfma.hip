@@ -834,286 +834,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         }
     }
 
-    // --------------------------------------------------------------------- current keys ----
-    if (a.n_cur > 0) {
-        const uint16_t *k_base = static_cast<const uint16_t *>(a.k_cur) + head_off;
-        const uint16_t *v_base = static_cast<const uint16_t *>(a.v_cur) + head_off;
-        // B operands: the raw (unrotated, unscaled) bf16 queries.
-#pragma unroll
-        for (int rb = 0; rb < kRB; ++rb) {
-            int64_t row = wave_row0 + 32 * rb + n;
-            row = row < a.m ? row : a.m - 1;
-            const uint16_t *src = q_base + row * a.q_stride_token + 8 * hh;
-#pragma unroll
-            for (int s = 0; s < 8; ++s) qop[rb][s] = *reinterpret_cast<const u32x4 *>(src + 16 * s);
-        }
-        // V^T staging: two buffers of 128 channel rows x 32 tokens (bf16), reusing the query staging area.
-        __syncthreads();
-        // Row of a channel: 32 tokens in the order [16-token half][lane half hh][g][4], so that the eight
-        // tokens a lane feeds to one P*V MFMA (16 sl + 8 g + 4 hh + 0..3, g = 0, 1) are 16 contiguous bytes;
-        // rows are 20 words apart (16-byte aligned, banks spread).
-        constexpr int kVtW = 20;
-        auto vt = [&](int i) -> uint16_t * { return reinterpret_cast<uint16_t *>(q_stage + (i & 1) * D * kVtW); };
-        // Under the causal mask the tiles past the last row of this workgroup are skipped by all its waves.
-        int64_t n_keys = a.n_cur;
-        if (a.causal) {
-            int64_t last_row = (int64_t)rblk * kRowsPerBlock + kRowsPerBlock - 1;
-            last_row = last_row < a.m ? last_row : a.m - 1;
-            const int64_t upto = last_row + (a.n_cur - a.m) + 1;
-            n_keys = upto < n_keys ? upto : n_keys;
-        }
-        const int n_tiles = (int)((n_keys + kTileTokens - 1) / kTileTokens);
-        constexpr int kVtIters = 16 * 32 / kThreads;     // 16 channel octets x 32 tokens per tile
-        constexpr int kVtOcts = kThreads / 32;
-        u32x4 pre_vt[kVtIters];
-        const int ld_key = tid & 31, ld_oct = tid >> 5;  // octets ld_oct (+ kVtOcts)
-        const int vt_pos = 16 * (ld_key >> 4) + 8 * ((ld_key >> 2) & 1) + 4 * ((ld_key >> 3) & 1) + (ld_key & 3);
-        auto prefetch_v = [&](int tile) {
-            int64_t key = (int64_t)tile * kTileTokens + ld_key;
-            key = key < a.n_cur ? key : a.n_cur - 1;
-            const uint16_t *src = v_base + key * a.stride_token;
-#pragma unroll
-            for (int it = 0; it < kVtIters; ++it) pre_vt[it] = *reinterpret_cast<const u32x4 *>(src + 8 * (ld_oct + kVtOcts * it));
-        };
-        auto commit_v = [&](uint16_t *buf) {
-#pragma unroll
-            for (int it = 0; it < kVtIters; ++it) {
-                const uint32_t ws[4] = {pre_vt[it].x, pre_vt[it].y, pre_vt[it].z, pre_vt[it].w};
-#pragma unroll
-                for (int el = 0; el < 8; ++el) {
-                    const int ch = 8 * (ld_oct + kVtOcts * it) + el;
-                    const uint16_t val = (uint16_t)(el & 1 ? ws[el >> 1] >> 16 : ws[el >> 1] & 0xffffu);
-                    buf[ch * (2 * kVtW) + vt_pos] = val;
-                }
-            }
-        };
-        // Key rows: the workgroup loads a tile once, 16 consecutive lanes per 256-byte row (every wave
-        // taking its A operands straight from global memory costs one cache access per lane and four
-        // times the traffic), stages it in LDS one tile ahead of the values, rows kQRowWords words apart,
-        // and each wave reads its operands from there: lane (n, hh) takes 16 bytes at 32 slab + 16 hh of row n.
-        constexpr int kKtIters = 32 * 16 / kThreads;      // 16-byte pieces per thread
-        uint32_t *const k_stage = q_stage + 2 * D * kVtW; // behind the two V^T buffers
-        auto kt = [&](int i) -> uint32_t * { return k_stage + (i & 1) * kTileTokens * kQRowWords; };
-        u32x4 pre_k[kKtIters];
-        auto prefetch_k = [&](int tile) {
-#pragma unroll
-            for (int it = 0; it < kKtIters; ++it) {
-                const int c = tid + kThreads * it;
-                int64_t key = (int64_t)tile * kTileTokens + (c >> 4);
-                key = key < a.n_cur ? key : a.n_cur - 1;
-                pre_k[it] = *reinterpret_cast<const u32x4 *>(k_base + key * a.stride_token + 8 * (c & 15));
-            }
-        };
-        auto commit_k = [&](uint32_t *buf) {
-#pragma unroll
-            for (int it = 0; it < kKtIters; ++it) {
-                const int c = tid + kThreads * it;
-                *reinterpret_cast<u32x4 *>(buf + (c >> 4) * kQRowWords + 4 * (c & 15)) = pre_k[it];
-            }
-        };
-        u32x4 kop[8];
-        auto load_kop = [&](int tile) {
-            const uint32_t *src = kt(tile) + n * kQRowWords + 4 * hh;
-#pragma unroll
-            for (int slab = 0; slab < 8; ++slab) kop[slab] = *reinterpret_cast<const u32x4 *>(src + 8 * slab);
-        };
-        auto score_cur = [&](int tile, float (&e)[kRB][16], float (&tmax)[kRB]) {
-            f32x16 s[kRB];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[rb][v] = 0.0f;
-            load_kop(tile);
-#pragma unroll
-            for (int slab = 0; slab < 8; ++slab) {
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) s[rb] = mfma_bf16(kop[slab], qop[rb][slab], s[rb]);
-            }
-            const int64_t key_base = (int64_t)tile * kTileTokens + 4 * hh;
-            const bool edge = a.causal != 0 || (int64_t)(tile + 1) * kTileTokens > a.n_cur;
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) e[rb][v] = fmaf(s[rb][v], c_log, -m_ref[rb]);
-                if (edge) {
-                    // keys this row sees: all of them, or under the causal mask those up to its own position
-                    int64_t visible = a.n_cur;
-                    if (a.causal) {
-                        const int64_t upto = wave_row0 + 32 * rb + n + (a.n_cur - a.m) + 1;
-                        visible = upto < visible ? upto : visible;
-                    }
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int64_t kk = key_base + 8 * (v >> 2) + (v & 3);
-                        e[rb][v] = kk < visible ? e[rb][v] : kMaskBias;
-                    }
-                }
-                float mx = fmaxf(e[rb][0], e[rb][1]);
-#pragma unroll
-                for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(e[rb][v], e[rb][v + 1]));
-                tmax[rb] = max_halves(mx);
-            }
-        };
-        auto pv_cur = [&](int tile, const float (&e)[kRB][16]) {
-            u32x4 pop[kRB][2];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-                float lsum = 0.0f;
-                uint32_t pw[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float p0 = __builtin_amdgcn_exp2f(e[rb][2 * i]);
-                    const float p1 = __builtin_amdgcn_exp2f(e[rb][2 * i + 1]);
-                    lsum += p0 + p1;
-                    pw[i] = pack_bf16(p0, p1);
-                }
-                l_r[rb] += lsum;
-                pop[rb][0].x = pw[0]; pop[rb][0].y = pw[1]; pop[rb][0].z = pw[2]; pop[rb][0].w = pw[3];
-                pop[rb][1].x = pw[4]; pop[rb][1].y = pw[5]; pop[rb][1].z = pw[6]; pop[rb][1].w = pw[7];
-            }
-            // V^T from LDS: tokens 16 sl + 4 hh + 0..3 and 16 sl + 8 + 4 hh + 0..3
-            const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(vt(tile));
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t *rowp = vsrc + (32 * b + n) * kVtW + 4 * hh;
-#pragma unroll
-                for (int sl = 0; sl < 2; ++sl) {
-                    const u32x4 vop = *reinterpret_cast<const u32x4 *>(rowp + 8 * sl);
-#pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) o[b][rb] = mfma_bf16(vop, pop[rb][sl], o[b][rb]);
-                }
-            }
-        };
-
-        // One pipeline iteration: the score MFMAs of tile + 1 are interleaved with the exponentials of
-        // `tile`, the P*V MFMAs of `tile` with the scaling and masking of tile + 1 (same pattern as the
-        // cached-key loop, without unpacking).  On entry e holds tile's scores minus the reference and LDS
-        // the key rows of tile + 1 and the values of `tile`; on exit e and tmax describe tile + 1.
-        auto fused_cur = [&](int tile, float (&e)[kRB][16], float (&tmax)[kRB]) {
-            f32x16 s[kRB];
-            float lsum[kRB] = {};
-            uint32_t pw[kRB][8];
-            auto exp_chunk = [&](auto c_) {
-                constexpr int C = decltype(c_)::value;
-                constexpr int RB = (C * kRB) / 8, I0 = (C * kRB) % 8;
-#pragma unroll
-                for (int i = I0; i < I0 + kRB; ++i) {
-                    float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
-                    float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
-                    asm volatile("" : "+v"(p0), "+v"(p1));   // keeps the exponentials in this chunk
-                    lsum[RB] += p0 + p1;
-                    pw[RB][i] = pack_bf16(p0, p1);
-                }
-            };
-            f32x16 zero;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            load_kop(tile + 1);
-            // V^T operands of this tile: requested now, used after the score MFMAs
-            u32x4 vop[4][2];
-            {
-                const uint32_t *vsrc = reinterpret_cast<const uint32_t *>(vt(tile)) + n * kVtW + 4 * hh;
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-#pragma unroll
-                    for (int sl = 0; sl < 2; ++sl) vop[b][sl] = *reinterpret_cast<const u32x4 *>(vsrc + 32 * b * kVtW + 8 * sl);
-            }
-            KVQ_CHUNK_FENCE();
-            static_for<8>([&](auto s_) {
-                constexpr int SLAB = decltype(s_)::value;
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) s[rb] = mfma_bf16(kop[SLAB], qop[rb][SLAB], SLAB == 0 ? zero : s[rb]);
-                // Instruction selection orders nodes without side effects by data dependence only: the empty
-                // statements tie this slab's MFMAs and this chunk's exponentials to program order.
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) asm volatile("" : "+a"(s[rb]));
-                exp_chunk(IntC<SLAB>{});
-                KVQ_CHUNK_FENCE();
-            });
-            u32x4 pop[kRB][2];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-                l_r[rb] += lsum[rb];
-                pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
-                pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
-            }
-            KVQ_CHUNK_FENCE();
-            float mx[kRB];
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
-            static_for<4>([&](auto b_) {
-                constexpr int B = decltype(b_)::value;
-#pragma unroll
-                for (int sl = 0; sl < 2; ++sl) {
-#pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) o[B][rb] = mfma_bf16(vop[B][sl], pop[rb][sl], o[B][rb]);
-                }
-                constexpr int RB = (B * 4 * kRB) / 16, V0 = (B * 4 * kRB) % 16;   // one quarter of the next tile
-#pragma unroll
-                for (int v = V0; v < V0 + 4 * kRB; ++v) e[RB][v] = fmaf(s[RB][v], c_log, -m_ref[RB]);
-#pragma unroll
-                for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
-                KVQ_CHUNK_FENCE();
-            });
-            // Tiles that hold keys some row must not see (the ragged last tile; every tile under the causal
-            // mask) are masked after the fact: a uniform branch at the end of the iteration, not inside it.
-            const bool edge = a.causal != 0 || (int64_t)(tile + 2) * kTileTokens > a.n_cur;
-            if (edge) {
-                const int key_base = (tile + 1) * kTileTokens + 4 * hh;
-#pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) {
-                    int visible = (int)a.n_cur;
-                    if (a.causal) {
-                        const int64_t upto = wave_row0 + 32 * rb + n + (a.n_cur - a.m) + 1;
-                        visible = upto < visible ? (int)upto : visible;
-                    }
-                    float m2 = -INFINITY;
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        e[rb][v] = key_base + 8 * (v >> 2) + (v & 3) < visible ? e[rb][v] : kMaskBias;
-                        m2 = fmaxf(m2, e[rb][v]);
-                    }
-                    mx[rb] = m2;
-                }
-            }
-#pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(mx[rb]);
-        };
-
-        prefetch_v(0);
-        prefetch_k(0);
-        commit_v(vt(0));
-        commit_k(kt(0));
-        __syncthreads();
-        if (n_tiles > 1) prefetch_k(1);
-        float e[kRB][16], tmax[kRB];
-        int tile = 0;
-        score_cur(0, e, tmax);
-        if (n_tiles > 1) {   // the key rows run one tile ahead of the values
-            commit_k(kt(1));
-            __syncthreads();
-        }
-        bool done = false;
-        while (!done) {
-            move_reference(e, tmax);
-            for (;;) {
-                if (tile + 1 >= n_tiles) {
-                    pv_cur(tile, e);
-                    done = true;
-                    break;
-                }
-                const bool k_more = tile + 2 < n_tiles;
-                prefetch_v(tile + 1);
-                if (k_more) prefetch_k(tile + 2);
-                fused_cur(tile, e, tmax);
-                commit_v(vt(tile + 1));
-                if (k_more) commit_k(kt(tile + 2));   // the buffer of tile's rows: consumed one iteration ago
-                __syncthreads();
-                ++tile;
-                if (__any(over_threshold(tmax))) break;
-            }
-        }
-    }
+#include "kvq_mfma_current_phase.inc"
 
     // ------------------------------------------------------------------------- epilogue ----
     uint16_t *out_base = static_cast<uint16_t *>(a.out) + qhead_off;

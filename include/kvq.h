@@ -23,7 +23,10 @@
  *   - Launching calls are asynchronous on the HIP stream passed as `hip_stream`
  *     (a hipStream_t cast to void*; NULL is the default stream).  They return after
  *     argument validation and enqueue.  Calls that touch the same cache must be
- *     stream-ordered by the caller.
+ *     stream-ordered by the caller.  They enqueue kernels only (no allocation, no
+ *     memset, no synchronisation), so they may be recorded into a HIP graph once each
+ *     kernel has been launched outside a capture; the host-side counters of the
+ *     cache (length, window, blocks) change at call time, not at replay.
  *   - Errors are returned as kvq_status; nothing aborts or throws.  On any error
  *     nothing has been enqueued and the cache is unchanged.
  *   - Tensors are [token][head][channel] with element strides `stride_token`,

@@ -456,3 +456,41 @@ def test_attention_diagnostics(P, name, io, bits, group, fp8):
     torch.cuda.synchronize()
     got = diag.cpu().numpy()
     assert np.all(got[:, :, :2] == 0.0) and np.all(np.abs(got[:, :, 2:]) <= 1e-9)
+
+
+def test_attention_replayed_from_a_graph(P):
+    """The launching calls only enqueue kernels on the stream they are given (no allocation, no memset,
+    no host synchronisation), so a serving loop can capture them: a captured quantize-free step (attention
+    over a filled cache) is replayed three times with new queries, eager work in between, and every replay
+    must equal the eager result bit for bit and the oracle to the usual bar."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, n_cached, n_cur, m = 2, 700, 130, 300
+    cache = P.make_cache(w, n_cached, heads=heads)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    krd, vrd = P.to_dev(kr, "bf16"), P.to_dev(vr, "bf16")
+    q_all = wl.chunk_q(w, heads=range(heads))
+    qd = P.to_dev(q_all[:m], "bf16")
+    out = torch.empty_like(qd)
+    mass = torch.empty((heads, m), dtype=torch.float32, device=P.DEV)
+    B.kvq_chunk_attention(cache, 0, n_cached, qd, krd, vrd, out, mass)      # first launch outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.kvq_chunk_attention(cache, 0, n_cached, qd, krd, vrd, out, mass)
+    for rep in range(3):
+        q = q_all[rep * 100:rep * 100 + m]
+        qd.copy_(P.to_dev(q, "bf16"))
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_mass = out.float().cpu().numpy().astype(np.float64), mass.cpu().numpy().astype(np.float64)
+        eager_out, eager_mass = torch.empty_like(qd), torch.empty_like(mass)
+        B.kvq_chunk_attention(cache, 0, n_cached, qd, krd, vrd, eager_out, eager_mass)
+        torch.cuda.synchronize()
+        assert torch.equal(eager_out, out) and torch.equal(eager_mass, mass), "replay %d differs from the eager call" % rep
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1)
+        P.assert_attention_close(got, got_mass, ref, mass_ref, P.TOL_OUT_BF16, "graph replay %d" % rep)

@@ -57,6 +57,13 @@
 #ifndef KVQ_Q_LOW_RESIDENT_SLABS
 #define KVQ_Q_LOW_RESIDENT_SLABS 4
 #endif
+// 1 (2-bit caches only): the low query part is an FP8 E4M3 operand with one power-of-two scale per row and
+// meets the key codes in v_mfma_scale_f32_32x32x64_f8f6f4 (64 channels per instruction at twice the
+// 16-bit rate): 4 MFMAs per key tile instead of 16, the whole low part resident in 32 accumulation
+// registers.  0: f16 low part as for 4-bit caches.
+#ifndef KVQ_Q_LOW_FP8
+#define KVQ_Q_LOW_FP8 1
+#endif
 
 namespace kvq {
 namespace {
@@ -130,6 +137,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     // ---------------------------------------------------------------- query preparation ----
     // kPrepLanes adjacent lanes rotate one query row of the block: q~ = Hn q * softmax_scale * log2(e),
     // split into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
+    constexpr bool kLoFp8 = KVQ_Q_LOW_PART && KVQ_Q_LOW_FP8 && BITS == 2;
+    constexpr bool kLoF16 = KVQ_Q_LOW_PART && !kLoFp8;
     constexpr int kPrepLanes = kThreads / kRowsPerBlock;   // 1 or 2
     constexpr int kPrepCh = D / kPrepLanes;                 // channels per lane
     u32x4 qop[kRB][8];  // B operands of the score MFMA: lane (n, hh) holds channels 16*slab + 8*hh .. +7 of rows n + 32 rb
@@ -202,6 +211,46 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 qop[rb][s] = *reinterpret_cast<const u32x4 *>(hsrc + 32 * rb * kQRowWords + 8 * s);
         __syncthreads();
         float ssum = 0.0f, ssum_w = 0.0f;   // sum of q~ (true scale), sum of the weighted operand values
+        if constexpr (kLoFp8) {
+            static_assert(!kLoFp8 || kPrepLanes == 1, "one lane prepares a whole row");
+            // Low parts at true scale (the weight 4^g of the high operand taken out again: exact), their
+            // largest magnitude, and from it the row's power-of-two scale: the largest low part lands in
+            // [128, 256), inside the E4M3 range.
+            float lo_t[kPrepCh], mx = 0.0f;
+#pragma unroll
+            for (int c = 0; c < kPrepCh; c += 2) {
+                const uint32_t hi = pack_f16(x[c], x[c + 1]);
+                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(c)));   // both channels share a class
+                lo_t[c] = (x[c] - f16_lo(hi)) * wgt;
+                lo_t[c + 1] = (x[c + 1] - f16_hi(hi)) * wgt;
+                mx = fmaxf(mx, fmaxf(fabsf(lo_t[c]), fabsf(lo_t[c + 1])));
+                ssum_w += f16_lo(hi) + f16_hi(hi);
+                ssum += (f16_lo(hi) + f16_hi(hi)) * wgt;
+            }
+            const int ex = mx > 0.0f ? (int)((__float_as_uint(mx) >> 23) & 0xffu) - 127 - 7 : 0;   // floor(log2 mx) - 7
+            const float down = __uint_as_float((uint32_t)(127 - ex) << 23), up = __uint_as_float((uint32_t)(127 + ex) << 23);
+            // Operand order: MFMA j (channels of key words 2 j, 2 j + 1), lane half hh, register r8, byte b hold
+            // the channel whose code the key unpacking puts into the same byte.
+#pragma unroll
+            for (int w = 0; w < 32; ++w) {
+                const int j = w >> 4, hw = (w >> 3) & 1, r8 = w & 7;
+                float v[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int slab = 2 * (2 * j + (r8 >> 2)) + (b & 1);
+                    v[b] = lo_t[16 * slab + 8 * hw + 2 * (r8 & 3) + (b >> 1)] * down;
+                }
+                int word = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
+                word = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], word, true);
+                dst[w] = (uint32_t)word;
+                float dec = 0.0f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) dec += e4m3_to_float((uint8_t)((uint32_t)word >> (8 * b)));
+                ssum += dec * up;      // the sums follow the operands the MFMAs will see
+                ssum_w += dec * up;
+            }
+            row_scal[4 * prow + 3] = __int_as_float(127 + ex);
+        } else {
 #pragma unroll
         for (int i = 0; i < kPrepCh / 8; ++i) {
             uint32_t lo[4];
@@ -222,6 +271,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             u32x4 w;
             w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
             *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+        }
         }
         if constexpr (kPrepLanes == 2) {
             ssum += __shfl_xor(ssum, 1);
@@ -271,7 +321,39 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
 
-    constexpr int kLoRes = KVQ_Q_LOW_PART ? KVQ_Q_LOW_RESIDENT_SLABS : 0;
+    // FP8 low part: B operands of the two 64-channel MFMAs per 32-row block, and the rows' scale bytes
+    i32x8 lo8[kRB][2];
+    int lo_scale[kRB];
+    if constexpr (kLoFp8) {
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+            const uint32_t *src = q_stage + (wave * kRowsPerWave + 32 * rb + n) * kQRowWords + 8 * hh;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const u32x4 w0 = *reinterpret_cast<const u32x4 *>(src + 16 * j);
+                const u32x4 w1 = *reinterpret_cast<const u32x4 *>(src + 16 * j + 4);
+                lo8[rb][j] = i32x8{(int)w0.x, (int)w0.y, (int)w0.z, (int)w0.w, (int)w1.x, (int)w1.y, (int)w1.z, (int)w1.w};
+                asm volatile("" : "+a"(lo8[rb][j]));
+            }
+            lo_scale[rb] = __float_as_int(row_scal[4 * (wave * kRowsPerWave + 32 * rb + n) + 3]);
+        }
+    }
+    // Low-part MFMAs of 64 channels (key words 2 J and 2 J + 1): the codes become FP8 values 4 + code, four to
+    // a register, in the byte order the low operand was written in.
+    auto low_part_fp8 = [&](auto j_, const uint32_t (&kw)[WPL], f32x16 (&sn)[kRB]) {
+        constexpr int J = decltype(j_)::value;
+        i32x8 a8;
+#pragma unroll
+        for (int r8 = 0; r8 < 8; ++r8) {
+            const uint32_t w = kw[(2 * J + (r8 >> 2)) % WPL];
+            const uint32_t sh = (r8 & 3) == 0 ? w << 1 : w >> (2 * (r8 & 3) - 1);
+            a8[r8] = (int)((sh & 0x06060606u) | 0x48484848u);
+        }
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
+            sn[rb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, lo8[rb][J], sn[rb], 0, 0, 0, 0x7f, 0, lo_scale[rb]);
+    };
+    constexpr int kLoRes = kLoF16 ? KVQ_Q_LOW_RESIDENT_SLABS : 0;
     u32x4 lo_res[kRB][kLoRes > 0 ? kLoRes : 1];
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb)
@@ -466,23 +548,25 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
                 const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
-#if KVQ_Q_LOW_PART
                 u32x4 lo[kRB];
-                if constexpr (SLAB >= kLoRes) {
+                if constexpr (kLoF16 && SLAB >= kLoRes) {
 #pragma unroll
                     for (int rb = 0; rb < kRB; ++rb) lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
                 }
-#endif
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
-#if KVQ_Q_LOW_PART
+                if constexpr (kLoF16) {
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) {
-                    if constexpr (SLAB < kLoRes) sn[rb] = mfma_f16(kop, lo_res[rb][SLAB], sn[rb]);
-                    else sn[rb] = mfma_f16(kop, lo[rb], sn[rb]);
+                    for (int rb = 0; rb < kRB; ++rb) {
+                        if constexpr (SLAB < kLoRes) sn[rb] = mfma_f16(kop, lo_res[rb][SLAB], sn[rb]);
+                        else sn[rb] = mfma_f16(kop, lo[rb], sn[rb]);
+                    }
                 }
-#endif
             });
+            if constexpr (kLoFp8) {
+                low_part_fp8(IntC<0>{}, kw, sn);
+                low_part_fp8(IntC<1>{}, kw, sn);
+            }
         };
         // e = scale_i * raw - reference; returns the tile maximum of e per row block.
         auto finalize_tile = [&](int t, const f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB]) {
@@ -638,13 +722,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 constexpr int SLAB = decltype(s_)::value;
                 // This slab's low query parts are requested now and multiplied one chunk later, so that no
                 // MFMA of the iteration waits for LDS: the high parts and the key codes are in registers.
-#if KVQ_Q_LOW_PART
-                if constexpr (SLAB >= kLoRes) {
+                if constexpr (kLoF16 && SLAB >= kLoRes) {
 #pragma unroll
                     for (int rb = 0; rb < kRB; ++rb)
                         lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
                 }
-#endif
                 if constexpr (SLAB == 5) {  // value codes and key scales for the second half of the iteration
                     const uint32_t *src = bufc + St::kV + tlc * 64 * WPL + lane * WPL;
 #pragma unroll
@@ -663,31 +745,33 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
                 if constexpr (SLAB >= 1) {
-#if KVQ_Q_LOW_PART
+                    if constexpr (kLoF16) {
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) {
-                        if constexpr (SLAB - 1 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][SLAB - 1], sn[rb]);
-                        else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                        for (int rb = 0; rb < kRB; ++rb) {
+                            if constexpr (SLAB - 1 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][SLAB - 1], sn[rb]);
+                            else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                        }
                     }
-#endif
+                    if constexpr (kLoFp8 && SLAB == 4) low_part_fp8(IntC<0>{}, pf.kw, sn);   // key words 0, 1: slabs 0..3
                     exp_chunk(IntC<SLAB - 1>{});
                 }
-#if KVQ_Q_LOW_PART
-                kop_prev = kop;
-                if constexpr (SLAB >= kLoRes) {
+                if constexpr (kLoF16) {
+                    kop_prev = kop;
+                    if constexpr (SLAB >= kLoRes) {
 #pragma unroll
-                    for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
+                        for (int rb = 0; rb < kRB; ++rb) lo_cur[rb] = lo_nxt[rb];
+                    }
                 }
-#endif
                 KVQ_CHUNK_FENCE();
             });
-#if KVQ_Q_LOW_PART
+            if constexpr (kLoF16) {
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) {
-                if constexpr (7 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][7], sn[rb]);
-                else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                for (int rb = 0; rb < kRB; ++rb) {
+                    if constexpr (7 < kLoRes) sn[rb] = mfma_f16(kop_prev, lo_res[rb][7], sn[rb]);
+                    else sn[rb] = mfma_f16(kop_prev, lo_cur[rb], sn[rb]);
+                }
             }
-#endif
+            if constexpr (kLoFp8) low_part_fp8(IntC<1>{}, pf.kw, sn);
             exp_chunk(IntC<7>{});
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {

@@ -3,6 +3,7 @@
 // small wave-level utilities.  Included inside namespace kvq { namespace { ... } } of each kernel file.
 #pragma once
 
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;

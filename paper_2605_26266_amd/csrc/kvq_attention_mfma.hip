@@ -28,7 +28,9 @@
 // to fp32 accuracy.  The correction therefore costs no vector instruction at all; what is left per
 // score is one fused multiply-add (scale, minus the reference maximum), the exponential and the P*V
 // bookkeeping.  On the value side the value scale is folded into the probability before it is rounded
-// to bf16, and the zero-point/BASE term is a per-row scalar tau_m = sum_i p'_mi (BASE + z_i),
+// to bf16 -- as log2(value scale) / scale_i in two spare slots of that same constant-term operand, so
+// that 2^e already is p' = p * value scale and the row sum takes p back as p' / value scale in one fused
+// multiply-add -- and the zero-point/BASE term is a per-row scalar tau_m = sum_i p'_mi (BASE + z_i),
 // accumulated from the rounded probabilities (dot2 on bf16 pairs) so that it cancels exactly.  The
 // cached part of O lives in the rotated basis; when the cached keys are done the accumulators are
 // rotated back in registers (six butterfly stages inside the lane, one between the lane halves) and
@@ -80,7 +82,7 @@ template <int BITS> struct Stage {
     static constexpr int kV = kCodeWords;
     static constexpr int kCop = 2 * kCodeWords;                 // [tile][lane][4]  constant-term A operand
     static constexpr int kKScale = kCop + kStageTiles * 64 * 4; // [tile][hh][16]   float
-    static constexpr int kVScale = kKScale + kStageKeys;        // [tile][hh][16]   float
+    static constexpr int kVScale = kKScale + kStageKeys;        // [tile][hh][16]   float: 1 / (value scale * 4^g)
     static constexpr int kVzHi = kVScale + kStageKeys;          // [tile][hh][8]    bf16 pairs
     static constexpr int kVzLo = kVzHi + kStageKeys / 2;
     static constexpr int kFlags = kVzLo + kStageKeys / 2;       // 2 words: "some low zero-point part is nonzero"
@@ -308,9 +310,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const uint32_t one = 0x3f80u;
         u32x4 w0, w1;
         w0.x = s_h | ((uint32_t)s_m << 16); w0.y = s_l | ((uint32_t)s_h << 16);
-        w0.z = s_m | ((uint32_t)s_l << 16); w0.w = one;
+        w0.z = s_m | ((uint32_t)s_l << 16); w0.w = one | (one << 16);
         w1.x = n_h | ((uint32_t)n_l << 16); w1.y = w1.x;
-        w1.z = w_h | ((uint32_t)w_m << 16); w1.w = w_l;
+        w1.z = w_h | ((uint32_t)w_m << 16); w1.w = w_l | (one << 16);
         rowop[rb] = hh ? w1 : w0;
     }
     const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
@@ -340,6 +342,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     }
     // Low-part MFMAs of 64 channels (key words 2 J and 2 J + 1): the codes become FP8 values 4 + code, four to
     // a register, in the byte order the low operand was written in.
+    // (mask in a scalar, base in a vector register: the form v_and_or_b32 can encode)
+    uint32_t f8_mask = 0x06060606u, f8_base = 0x48484848u;
+    asm volatile("" : "+s"(f8_mask));
+    asm volatile("" : "+v"(f8_base));
     auto low_part_fp8 = [&](auto j_, const uint32_t (&kw)[WPL], f32x16 (&sn)[kRB]) {
         constexpr int J = decltype(j_)::value;
         i32x8 a8;
@@ -347,7 +353,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         for (int r8 = 0; r8 < 8; ++r8) {
             const uint32_t w = kw[(2 * J + (r8 >> 2)) % WPL];
             const uint32_t sh = (r8 & 3) == 0 ? w << 1 : w >> (2 * (r8 & 3) - 1);
-            a8[r8] = (int)((sh & 0x06060606u) | 0x48484848u);
+            a8[r8] = (int)((sh & f8_mask) | f8_base);
         }
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb)
@@ -455,6 +461,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 if (ld_half == 0) {
                     pre_a = cv.k_negzero[meta0 + tok];
                     pre_b = cv.k_scale[meta0 + tok];
+                    pre_c = cv.v_scale[meta0 + tok];
                 } else {
                     pre_a = cv.k_scale[meta0 + tok];
                     pre_b = cv.v_scale[meta0 + tok];
@@ -465,6 +472,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 if (ld_half == 0) {
                     pre_a = -(bf16_val(cv.k_zero16[meta0 + tok]) + Unpack<BITS>::kStoredOffset);
                     pre_b = ks;
+                    pre_c = e4m3_to_float(cv.v_scale8[meta0 + tok]);
                 } else {
                     pre_a = ks;
                     pre_b = e4m3_to_float(cv.v_scale8[meta0 + tok]);
@@ -485,6 +493,18 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             // Position of this key in the per-lane order of the score tile: [tile][hh][4 g + r].
             const int tl = ld_key >> 5, r = ld_key & 31;
             const int slot = tl * 32 + ((r >> 2) & 1) * 16 + 4 * (r >> 3) + (r & 3);
+            // The value scale (times the weight 4^g its key's probability carries, see below) is not multiplied
+            // into the probability: its logarithm is added to the score, as lambda / key scale in the two free
+            // slots of the constant-term operand (two bf16 pieces against ones), so that 2^e already is
+            // p * value scale; the row sum gets p back through the reciprocal kept in the kVScale array.
+            // Scales are clamped away from zero (an all-zero row has scale 0): such a key scores 0 and its
+            // value contributes 2^-64 p, as good as the exact 0.
+            const int g2 = 2 * value_register_class<BITS>(slot & 15);
+            const float vs_eff = ldexpf(fmaxf(ld_half == 0 ? pre_c : pre_b, 0x1p-64f), g2);
+            const float ks_eff = fmaxf(ld_half == 0 ? pre_b : pre_a, 0x1p-40f);
+            const float lam = pre_valid ? __log2f(vs_eff) / ks_eff : 0.0f;
+            const uint16_t lam_h = bf16_bits(lam);
+            const uint16_t lam_l = bf16_bits(lam - bf16_val(lam_h));
             u32x4 cop;
             if (ld_half == 0) {
                 // -zero in two bf16 pieces (exact for |.| < 2^16), and the window mask.
@@ -493,22 +513,21 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const uint16_t z_l = bf16_bits(nz - bf16_val(z_h));
                 cop.x = z_h | ((uint32_t)z_h << 16); cop.y = z_h | ((uint32_t)z_l << 16);
                 cop.z = z_l | ((uint32_t)z_l << 16);
-                cop.w = pre_valid ? 0u : (uint32_t)bf16_bits(kMaskBias);
-                reinterpret_cast<float *>(buf + St::kKScale)[slot] = pre_valid ? pre_b : 1.0f;
+                cop.w = (pre_valid ? 0u : (uint32_t)bf16_bits(kMaskBias)) | ((uint32_t)lam_h << 16);
+                reinterpret_cast<float *>(buf + St::kKScale)[slot] = pre_valid ? ks_eff : 1.0f;
             } else {
-                const float ks = pre_valid ? pre_a : 0.0f;
+                const float ks = pre_valid ? ks_eff : 0.0f;
                 const uint16_t k_h = bf16_bits(ks);
                 const uint16_t k_l = bf16_bits(ks - bf16_val(k_h));
                 const uint32_t nb = pre_valid ? (uint32_t)bf16_bits(-Unpack<BITS>::kKeyBase) : 0u;   // exact
                 cop.x = k_h | ((uint32_t)k_h << 16); cop.y = k_l | ((uint32_t)k_l << 16);
-                cop.z = nb | (nb << 16); cop.w = nb;
-                // Tokens outside the window get value scale 0: their probability is exactly 0, and whatever
-                // the storage holds there (it need not be initialised) must not turn that into a NaN.
+                cop.z = nb | (nb << 16); cop.w = nb | ((uint32_t)lam_l << 16);
+                // Tokens outside the window: the mask bias makes their probability exactly 0, and nothing
+                // derived from what the storage holds there (it need not be initialised) enters the tile.
                 // The probability of this key meets value codes unpacked with weight 4^-g: it carries 4^g
                 // (through the value scale), and tau's multiplier is BASE + 4^-g z.
-                const int g2 = 2 * value_register_class<BITS>(slot & 15);
                 const float vz = pre_valid ? Unpack<BITS>::kValueBase + ldexpf(pre_c - Unpack<BITS>::kStoredOffset, -g2) : 0.0f;
-                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? ldexpf(pre_b, g2) : 0.0f;
+                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? 1.0f / vs_eff : 0.0f;
                 const uint16_t v_h = bf16_bits(vz);
                 const uint16_t v_l = bf16_bits(vz - bf16_val(v_h));
                 reinterpret_cast<uint16_t *>(buf + St::kVzHi)[slot] = v_h;
@@ -588,16 +607,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 tmax[rb] = max_halves(mx);
             }
         };
-        // p = 2^e, partial sums, p' = p * value-scale rounded to bf16 (B operands), tau.
+        // p' = 2^e (the value scale is in e), partial sums of p' / value-scale, p' rounded to bf16 (B operands), tau.
         auto exp_tile = [&](int t, const float (&e)[kRB][16], u32x4 (&pop)[kRB][2]) {
             const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int pos = (t & 3) * 32 + hh * 16;
             const float *vsp = reinterpret_cast<const float *>(buf + St::kVScale) + pos;
-            float v_scale[16];
+            float v_inv[16];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const float4 c = *reinterpret_cast<const float4 *>(vsp + 4 * g);
-                v_scale[4 * g] = c.x; v_scale[4 * g + 1] = c.y; v_scale[4 * g + 2] = c.z; v_scale[4 * g + 3] = c.w;
+                v_inv[4 * g] = c.x; v_inv[4 * g + 1] = c.y; v_inv[4 * g + 2] = c.z; v_inv[4 * g + 3] = c.w;
             }
             uint32_t zh[8], zl[8];
             {
@@ -616,8 +635,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 for (int i = 0; i < 8; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[rb][2 * i]);
                     const float p1 = __builtin_amdgcn_exp2f(e[rb][2 * i + 1]);
-                    lsum += p0 + p1;
-                    pw[i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
+                    lsum = fmaf(p1, v_inv[2 * i + 1], fmaf(p0, v_inv[2 * i], lsum));
+                    pw[i] = pack_bf16(p0, p1);
                     tacc = dot2_bf16(pw[i], zh[i], tacc);
                     tacc = dot2_bf16(pw[i], zl[i], tacc);
                 }
@@ -676,13 +695,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             const int tln = (t + 1) & 3, tlc = t & 3;
             const int pos = tlc * 32 + hh * 16;
             // requests for this iteration's exponential work
-            float v_scale[16];
+            float v_inv[16];
             {
                 const float *vsp = reinterpret_cast<const float *>(bufc + St::kVScale) + pos;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const float4 c = *reinterpret_cast<const float4 *>(vsp + 4 * g);
-                    v_scale[4 * g] = c.x; v_scale[4 * g + 1] = c.y; v_scale[4 * g + 2] = c.z; v_scale[4 * g + 3] = c.w;
+                    v_inv[4 * g] = c.x; v_inv[4 * g + 1] = c.y; v_inv[4 * g + 2] = c.z; v_inv[4 * g + 3] = c.w;
                 }
             }
             uint32_t zh[8];
@@ -712,8 +731,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 for (int i = I0; i < I0 + kRB; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
                     const float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
-                    lsum[RB] += p0 + p1;
-                    pw[RB][i] = pack_bf16(p0 * v_scale[2 * i], p1 * v_scale[2 * i + 1]);
+                    lsum[RB] = fmaf(p1, v_inv[2 * i + 1], fmaf(p0, v_inv[2 * i], lsum[RB]));
+                    pw[RB][i] = pack_bf16(p0, p1);
                     tacc[RB] = dot2_bf16(pw[RB][i], zh[i], tacc[RB]);
                 }
             };

@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
                 for (int b = 0; b < 4; ++b) dec += e4m3_to_float((uint8_t)((uint32_t)word >> (8 * b)));
                 ssum += dec * up;      // the sums follow the operands the MFMAs will see
-                ssum_w += dec * up;
+                ssum_w += 2.0f * (dec * up);   // FP8 key values are 8 + code, twice the BASE the constant term takes off
             }
             row_scal[4 * prow + 3] = __int_as_float(127 + ex);
         } else {
@@ -340,10 +340,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             lo_scale[rb] = __float_as_int(row_scal[4 * (wave * kRowsPerWave + 32 * rb + n) + 3]);
         }
     }
-    // Low-part MFMAs of 64 channels (key words 2 J and 2 J + 1): the codes become FP8 values 4 + code, four to
+    // Low-part MFMAs of 64 channels (key words 2 J and 2 J + 1): the codes become FP8 values 8 + code, four to
     // a register, in the byte order the low operand was written in.
     // (mask in a scalar, base in a vector register: the form v_and_or_b32 can encode)
-    uint32_t f8_mask = 0x06060606u, f8_base = 0x48484848u;
+    uint32_t f8_mask = 0x03030303u, f8_base = 0x50505050u;
     asm volatile("" : "+s"(f8_mask));
     asm volatile("" : "+v"(f8_base));
     auto low_part_fp8 = [&](auto j_, const uint32_t (&kw)[WPL], f32x16 (&sn)[kRB]) {
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
         for (int r8 = 0; r8 < 8; ++r8) {
             const uint32_t w = kw[(2 * J + (r8 >> 2)) % WPL];
-            const uint32_t sh = (r8 & 3) == 0 ? w << 1 : w >> (2 * (r8 & 3) - 1);
+            const uint32_t sh = w >> (2 * (r8 & 3));   // no shift for the first code; w >> 2 is shared with the f16 unpacking
             a8[r8] = (int)((sh & f8_mask) | f8_base);
         }
 #pragma unroll

@@ -426,7 +426,6 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const int n_stages = (n_tiles + kStageTiles - 1) / kStageTiles;
         const int64_t head_tile0 = (int64_t)head * cv.cap_tiles;
         const int64_t meta0 = head_tile0 * kTileTokens;
-        const int64_t cap_tokens = cv.cap_tiles * kTileTokens;
 
         // ---- loader: global -> registers (prefetch), registers -> LDS (commit, builds the constants)
         constexpr int kCodeVecs = St::kCodeWords / 4;               // 16-byte vectors per tensor and stage
@@ -436,27 +435,38 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1; // one (key, operand half) per thread below 256
         const bool ld_meta = tid < 2 * kStageKeys;
+        // Ring arithmetic in 32 bits (the launcher sends caches of 2^30 tiles or more per head elsewhere): the
+        // stage's first physical tile is uniform, a thread adds its tile inside the stage and wraps once more.
+        const int cap = (int)cv.cap_tiles;
+        const int first_off = (int)(cs - t_first * kTileTokens);   // position of cache_start inside its tile
+        const int win_len = (int)a.cache_len;
+        const uint32_t *code_src[kCodeIters];
+        int code_tile[kCodeIters];
+#pragma unroll
+        for (int it = 0; it < kCodeIters; ++it) {
+            const int g = tid + kThreads * it, vec = g % kCodeVecs;
+            code_tile[it] = vec / (16 * WPL);
+            code_src[it] = (g < kCodeVecs ? cv.k_codes : cv.v_codes) + head_tile0 * (64 * WPL) + (vec % (16 * WPL)) * 4;
+        }
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
-            const int64_t tile0 = t_first + (int64_t)stage * kStageTiles;
-            const int64_t phys_tile0 = a.phys_tile_first + (int64_t)stage * kStageTiles;
+            int ring0 = (int)a.phys_tile_first + stage * kStageTiles;   // < 2 cap + 4: n_tiles <= cap + 1
+            ring0 -= ring0 >= cap ? cap : 0;
+            ring0 -= ring0 >= cap ? cap : 0;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
-                const int g = tid + kThreads * it, vec = g % kCodeVecs;
-                int64_t tile = phys_tile0 + vec / (16 * WPL);   // ring: at most two wraps (n_tiles <= cap_tiles + 1)
-                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
-                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
-                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // tiles past the window: any address inside the storage   // never read past the storage
-                const int64_t word = (head_tile0 + tile) * (64 * WPL) + (vec % (16 * WPL)) * 4;
-                pre_kv[it] = *reinterpret_cast<const u32x4 *>((g < kCodeVecs ? cv.k_codes : cv.v_codes) + word);
+                int tile = ring0 + code_tile[it];
+                tile -= tile >= cap ? cap : 0;    // tiles past the window wrap onto tiles of the storage: masked later
+                tile = tile < cap ? tile : cap - 1;   // (a ring of fewer than four tiles)
+                pre_kv[it] = *reinterpret_cast<const u32x4 *>(code_src[it] + (int64_t)tile * (64 * WPL));
             }
             if (!ld_meta) return;
-            int64_t tok = tile0 * kTileTokens + ld_key;
-            pre_in_window = (tok >= cs && tok < ce) ? 1u : 0u;
-            tok = phys_tile0 * kTileTokens + ld_key;
-            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
-            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
-            tok = tok < cap_tokens ? tok : cap_tokens - 1;
+            const int rel = stage * kStageKeys + ld_key - first_off;    // position inside the window
+            pre_in_window = (rel >= 0 && rel < win_len) ? 1u : 0u;
+            int mt = ring0 + (ld_key >> 5);
+            mt -= mt >= cap ? cap : 0;
+            mt = mt < cap ? mt : cap - 1;
+            const int64_t tok = (int64_t)mt * kTileTokens + (ld_key & 31);
             if constexpr (!FP8META) {
                 if (ld_half == 0) {
                     pre_a = cv.k_negzero[meta0 + tok];
@@ -502,7 +512,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             const int g2 = 2 * value_register_class<BITS>(slot & 15);
             const float vs_eff = ldexpf(fmaxf(ld_half == 0 ? pre_c : pre_b, 0x1p-64f), g2);
             const float ks_eff = fmaxf(ld_half == 0 ? pre_b : pre_a, 0x1p-40f);
-            const float lam = pre_valid ? __log2f(vs_eff) / ks_eff : 0.0f;
+            // (v_rcp_f32: one unit in the last place, far inside what lambda and the row sums need; both loader
+            // halves run the same instructions on the same inputs, so their pieces belong to one value)
+            const float lam = pre_valid ? __log2f(vs_eff) * __builtin_amdgcn_rcpf(ks_eff) : 0.0f;
             const uint16_t lam_h = bf16_bits(lam);
             const uint16_t lam_l = bf16_bits(lam - bf16_val(lam_h));
             u32x4 cop;
@@ -527,7 +539,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 // The probability of this key meets value codes unpacked with weight 4^-g: it carries 4^g
                 // (through the value scale), and tau's multiplier is BASE + 4^-g z.
                 const float vz = pre_valid ? Unpack<BITS>::kValueBase + ldexpf(pre_c - Unpack<BITS>::kStoredOffset, -g2) : 0.0f;
-                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? 1.0f / vs_eff : 0.0f;
+                reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? __builtin_amdgcn_rcpf(vs_eff) : 0.0f;
                 const uint16_t v_h = bf16_bits(vz);
                 const uint16_t v_l = bf16_bits(vz - bf16_val(v_h));
                 reinterpret_cast<uint16_t *>(buf + St::kVzHi)[slot] = v_h;

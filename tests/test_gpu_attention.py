@@ -272,6 +272,69 @@ def test_stream_append_then_attend(P):
     assert len(cache) == w.cached_tokens
 
 
+@pytest.mark.parametrize("bits", [2, 4])
+def test_all_zero_vectors_in_the_cache(P, bits):
+    """An all-zero key or value vector has scale 0 (Eq. 1 with an empty range): its key scores 0, its value
+    contributes nothing, and it still takes its share of the softmax mass.  The matrix-core path carries
+    log2(value scale) / key scale in the score, so both scales being 0 is the case to get right."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads, n_cached, n_cur, m = 2, 160, 48, 96
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    kc, vc = kc.copy(), vc.copy()
+    kc[[3, 40, 41, 159]] = 0.0          # zero keys (one of them with a zero value too)
+    vc[[5, 40, 100]] = 0.0
+    kc[7, 1] = 0.0                      # one head only
+    vc[64:96, 0] = 0.0                  # a whole tile of zero values in one head
+    cache = P.make_cache(w, 192, heads=heads)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    P.assert_quantized_equal(cache, kc, vc)
+    _, scales, _ = B.export_all(cache, 0)
+    assert float(scales.min()) == 0.0                             # the case this test is about
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.chunk_q(w, heads=range(heads))[:m]
+    for correction in (1, 0):
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction)
+        for fp32_kernel in (True, False):
+            out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction, fp32_kernel=fp32_kernel)
+            P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "zero vectors int%d" % bits)
+    # nothing but zero values: the output of the cached part is 0, the mass is not
+    vz = np.zeros_like(vc)
+    cache2 = P.make_cache(w, 192, heads=heads)
+    B.kvq_quantize_append(cache2, P.to_dev(kc, "bf16"), P.to_dev(vz, "bf16"))
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vz, kr, vr, bits, 1)
+    out, mass = P.run_gpu_attention(cache2, q, kr, vr, "bf16")
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "all values zero int%d" % bits)
+
+
+def test_ring_of_two_tiles(P):
+    """The smallest ring the matrix-core loader can meet: two tiles, a window that wraps, stages that reach
+    past the window on both sides."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads = 2
+    cache = P.make_cache(w, 64, heads=heads)
+    k, v = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=160)
+    q = wl.chunk_q(w, heads=range(heads))[:70]
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=33)
+    B.kvq_quantize_append(cache, P.to_dev(k[:64], "bf16"), P.to_dev(v[:64], "bf16"))
+    lo = 0
+    for step in range(3):
+        B.kvq_cache_evict(cache, 32)
+        lo += 32
+        B.kvq_quantize_append(cache, P.to_dev(k[lo + 32:lo + 64], "bf16"), P.to_dev(v[lo + 32:lo + 64], "bf16"))
+        kc, vc = k[lo:lo + 64], v[lo:lo + 64]
+        P.assert_quantized_equal(cache, kc, vc)
+        for (start, clen) in ((0, 64), (5, 50), (33, 31)):
+            ref, mass_ref, _ = oracle.chunk_attention(q, kc[start:start + clen], vc[start:start + clen], kr, vr, 2, 1)
+            for fp32_kernel in (False, True):
+                out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=start, cache_len=clen,
+                                                fp32_kernel=fp32_kernel)
+                P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "two-tile ring, step %d" % step)
+
+
 @pytest.mark.parametrize("group,fp8", [(None, False), (32, True)])
 def test_sliding_window_ring(P, group, fp8):
     """A cache with room for three 96-token chunks slides over nine chunks: evict the oldest, append the

@@ -883,19 +883,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             move_reference(e, tmax);
             // fast loop: nothing in here touches the accumulators except the MFMAs
             for (;;) {
-                if (t + 1 >= n_tiles) {
+                if (__builtin_expect(t + 1 >= n_tiles, 0)) {
                     exp_tile(t, e, pop);
                     pv_tile(t, pop);
                     done = true;
                     break;
                 }
-                if (t == t_open) {
+                if (__builtin_expect(t == t_open, 0)) {
                     open_stage((t + 2) >> 2);
                     t_open += 4;
                 }
                 fused_iteration(t, pf, sn, e, tmax, pop, lo_flag);
                 ++t;
-                if (__any(over_threshold(tmax) || lo_flag != 0u)) break;
+                if (__builtin_expect(__any(over_threshold(tmax) || lo_flag != 0u), 0)) break;
             }
         }
 

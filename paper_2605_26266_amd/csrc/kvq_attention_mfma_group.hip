@@ -733,19 +733,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         while (!done) {
             move_reference(e, tmax);
             for (;;) {
-                if (t + 1 >= n_tiles) {
+                if (__builtin_expect(t + 1 >= n_tiles, 0)) {
                     exp_tile(e, pop);
                     pv_tile(t, pop);
                     done = true;
                     break;
                 }
-                if (t == t_open) {
+                if (__builtin_expect(t == t_open, 0)) {
                     open_stage((t + 2) >> 2);
                     t_open += 4;
                 }
                 fused_iteration(t, pf, sn, e, tmax, pop);
                 ++t;
-                if (__any(over_threshold(tmax))) break;
+                if (__builtin_expect(__any(over_threshold(tmax)), 0)) break;
             }
         }
 

@@ -413,6 +413,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
 // well.  In that order a lane owns exactly one register position (reg = l mod 4, half = l / 4) of every
 // 16-wide slab of the key tile, so the key words are built with compile-time shifts and merged across the
 // 4 lanes of a quad with DPP.
+template <int CTRL> __device__ inline double dpp_f64(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = (int)b, hi = (int)(b >> 32);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+    return __longlong_as_double((long long)(((unsigned long long)h2 << 32) | l2));
+}
 __device__ inline uint32_t quad_or(uint32_t v)
 {
     v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
@@ -524,11 +532,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
                 lo = __builtin_fmin(lo, x[kRegs * g + i]);
                 hi = __builtin_fmax(hi, x[kRegs * g + i]);
             }
-#pragma unroll
-            for (int msk = 1; msk < 8; msk <<= 1) {
-                lo = __builtin_fmin(lo, __shfl_xor(lo, msk));
-                hi = __builtin_fmax(hi, __shfl_xor(hi, msk));
-            }
+            // across the vector's 8 lanes with data-parallel moves: neighbours, pairs, then the mirror image
+            // inside the 8 lanes (by then the four lanes of a quad agree, so lane l meets the other quad)
+            lo = __builtin_fmin(lo, dpp_f64<0xB1>(lo)); hi = __builtin_fmax(hi, dpp_f64<0xB1>(hi));      // quad_perm [1,0,3,2]
+            lo = __builtin_fmin(lo, dpp_f64<0x4E>(lo)); hi = __builtin_fmax(hi, dpp_f64<0x4E>(hi));      // quad_perm [2,3,0,1]
+            lo = __builtin_fmin(lo, dpp_f64<0x141>(lo)); hi = __builtin_fmax(hi, dpp_f64<0x141>(hi));    // row_half_mirror
             if (g == 0 || (l8 & (kG - 1)) == g) { lo_mine = lo; hi_mine = hi; }
         }
         double inv_mine, z_mine;
@@ -568,7 +576,10 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
             // domain), so they give the same codes as the double-precision statement of Eq. 1.
 #pragma unroll
             for (int i = kRegs * g; i < kRegs * (g + 1); ++i) {
-                const int c = (int)__builtin_rint(x[i] * inv) + zi;
+                // 1.5 * 2^52 added to a double below 2^31 in magnitude leaves its round-to-nearest-even integer in
+                // the low word of the sum (this file is compiled without contraction: product, then sum)
+                const double shifted = x[i] * inv + 6755399441055744.0;
+                const int c = (int)(uint32_t)__double_as_longlong(shifted) + zi;
                 code[i] = (uint32_t)(c < 0 ? 0 : (c > L ? L : c));   // one v_med3_i32
             }
         }

@@ -1,6 +1,7 @@
 // Matrix-core chunk attention for caches with several (scale, zero-point) groups per token:
-// BF16 I/O, head_dim 128, 2-bit codes, FP8-E4M3 scales and BF16 zero-points per group of 32 or 64
-// rotated channels (the storage format of the paper's "Effective bitwidth" formula, B + 24/g).
+// BF16 I/O, head_dim 128, FP8-E4M3 scales and BF16 zero-points per group of 32 or 64 rotated channels
+// (the storage format of the paper's "Effective bitwidth" formula, B + 24/g); 2-bit codes with either
+// group size, 4-bit codes with groups of 64.
 //
 // The structure is that of the per-token kernel (kvq_attention_mfma.hip: transposed products, one wave
 // per 64 query rows, lazy reference maximum, hand-interleaved pipeline); what changes is where the
@@ -855,14 +856,16 @@ template <int BITS, bool CORR, int G> hipError_t launch_group(const AttentionArg
 
 bool attention_mfma_group_supported(const CacheView &cv)
 {
-    return cv.head_dim == D && cv.io_dtype == KVQ_BF16 && cv.meta_format == KVQ_META_FP8_BF16 && cv.bits == 2 &&
-           (cv.group_size == 32 || cv.group_size == 64);
+    // (4-bit codes with groups of 32 need more LDS than a workgroup can have: vector kernel)
+    return cv.head_dim == D && cv.io_dtype == KVQ_BF16 && cv.meta_format == KVQ_META_FP8_BF16 &&
+           ((cv.bits == 2 && (cv.group_size == 32 || cv.group_size == 64)) || (cv.bits == 4 && cv.group_size == 64));
 }
 
 hipError_t launch_attention_mfma_group(const AttentionArgs &a, hipStream_t stream)
 {
     if (!attention_mfma_group_supported(a.cv)) return hipErrorInvalidValue;
     if (a.cache_len > (int64_t)0x3fffffff * kTileTokens) return hipErrorInvalidValue;
+    if (a.cv.bits == 4) return a.correction ? launch_group<4, true, 2>(a, stream) : launch_group<4, false, 2>(a, stream);
     if (a.cv.group_size == 32) return a.correction ? launch_group<2, true, 4>(a, stream) : launch_group<2, false, 4>(a, stream);
     return a.correction ? launch_group<2, true, 2>(a, stream) : launch_group<2, false, 2>(a, stream);
 }

@@ -152,7 +152,7 @@ def test_large_zero_points(P, bits):
 
 
 @pytest.mark.parametrize("correction", [1, 0])
-@pytest.mark.parametrize("bits,group", [(2, 32), (2, 64), (4, 32), (2, 128)])
+@pytest.mark.parametrize("bits,group", [(2, 32), (2, 64), (4, 32), (4, 64), (2, 128)])
 def test_group_wise_fp8_metadata(P, bits, group, correction):
     """The paper's default storage format: per-group FP8-E4M3 scale and BF16 zero-point; the correction is
     the per-group sum with the group norms of the rotated query (vector kernel)."""
@@ -234,6 +234,11 @@ def test_mid_group_wise_sampled_rows(P, group):
     """The paper's default format (INT2, FP8/BF16 metadata per 32 channels) at the mid shape on the matrix
     cores, and g = 64."""
     _sampled_case(P, "mid", 2, 48, [0, 23], group=group)
+
+
+def test_mid_group_wise_int4_sampled_rows(P):
+    """INT4 with FP8/BF16 metadata per 64 channels at the mid shape on the matrix cores."""
+    _sampled_case(P, "mid", 4, 48, [0, 23], group=64)
 
 
 @pytest.mark.parametrize("correction", [1, 0])

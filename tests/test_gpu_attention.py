@@ -277,6 +277,32 @@ def test_stream_append_then_attend(P):
     assert len(cache) == w.cached_tokens
 
 
+@pytest.mark.parametrize("k_mul,v_mul", [(1e-3, 1e3), (30.0, 1e-4), (1.0, 2.0 ** -20)])
+def test_extreme_key_and_value_scales(P, k_mul, v_mul):
+    """Keys and values far from unit scale: the matrix-core path carries log2(value scale) / key scale inside
+    the score accumulators, so tiny key scales and tiny or large value scales are its stress case."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, n_cached, n_cur, m = 2, 300, 64, 128
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    kc, vc = wl.round_to_bf16(kc * np.float32(k_mul)), wl.round_to_bf16(vc * np.float32(v_mul))
+    vc[::7] = wl.round_to_bf16(vc[::7] * np.float32(64.0))         # value scales that differ a lot between tokens
+    cache = P.make_cache(w, 320, heads=heads)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    P.assert_quantized_equal(cache, kc, vc)
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    kr, vr = wl.round_to_bf16(kr * np.float32(k_mul)), wl.round_to_bf16(vr * np.float32(v_mul))
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(min(1.0 / k_mul, 8.0)))
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, 2, 1)
+    scale = float(np.max(np.abs(ref))) or 1.0
+    for fp32_kernel in (True, False):
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", fp32_kernel=fp32_kernel)
+        # outputs of magnitude `scale`: the tolerance is the relative one of BF16 outputs
+        P.assert_attention_close(out / scale, mass, ref / scale, mass_ref, P.TOL_OUT_BF16,
+                                 "k x %g, v x %g" % (k_mul, v_mul))
+
+
 @pytest.mark.parametrize("bits", [2, 4])
 def test_all_zero_vectors_in_the_cache(P, bits):
     """An all-zero key or value vector has scale 0 (Eq. 1 with an empty range): its key scores 0, its value

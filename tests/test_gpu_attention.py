@@ -411,6 +411,64 @@ def test_sliding_window_ring(P, group, fp8):
     P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "ring, ragged eviction")
 
 
+def test_seeded_sweep_of_rings_and_windows(P):
+    """Forty seeded cases: ring capacities from 2 to 20 tiles, random evictions and appends (the storage wraps),
+    every cache format the matrix-core kernels serve, random windows, row counts, current-block sizes."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    rng = np.random.default_rng(7)
+    checked = 0
+    for case in range(40):
+        bits = int(rng.choice([2, 4]))
+        group, fp8 = [(None, False), (128, True), (32, True), (64, True)][int(rng.integers(0, 4))]
+        if bits == 4 and group == 32:
+            group = 64
+        w = wl.WORKLOADS["small"].with_bits(bits)
+        heads = int(rng.integers(1, 4))
+        cap = 32 * int(rng.integers(2, 21))
+        cache = P.make_cache(w, cap, heads=heads, group=group, fp8_meta=fp8)
+        src_k, src_v = wl.chunk_kv(w, case % 4, heads=range(heads), n_tokens=1024)
+        live_k, live_v, pos = [], [], 0
+        for _ in range(int(rng.integers(1, 7))):
+            if live_k and rng.random() < 0.7:
+                ev = min(len(live_k), 32 * int(rng.integers(1, 6)))
+                B.kvq_cache_evict(cache, ev)
+                live_k, live_v = live_k[ev:], live_v[ev:]
+            room = cap - len(live_k)
+            n_app = int(rng.integers(1, room + 1)) if room > 0 else 0
+            if n_app == 0 or pos + n_app > 1024:
+                continue
+            try:
+                B.kvq_quantize_append(cache, P.to_dev(src_k[pos:pos + n_app], "bf16"), P.to_dev(src_v[pos:pos + n_app], "bf16"))
+            except B.KvqError as e:        # the append would touch a tile that is still live
+                assert e.status == B.KVQ_ERR_CAPACITY
+                continue
+            live_k += list(src_k[pos:pos + n_app])
+            live_v += list(src_v[pos:pos + n_app])
+            pos += n_app
+        assert len(cache) == len(live_k)
+        if not live_k:
+            cache.close()
+            continue
+        kc, vc = np.stack(live_k), np.stack(live_v)
+        m, ncur = int(rng.integers(1, 200)), int(rng.integers(0, 100))
+        start = int(rng.integers(0, len(kc)))
+        clen = int(rng.integers(1, len(kc) - start + 1))
+        corr = int(rng.integers(0, 2))
+        q = wl.chunk_q(w, heads=range(heads))[:m]
+        kr, vr = wl.chunk_kv(w, 5, heads=range(heads), n_tokens=max(ncur, 1))
+        kr, vr = kr[:ncur], vr[:ncur]
+        kw = dict(group=group, fp8_meta=True) if fp8 else {}
+        ref, mass_ref, _ = oracle.chunk_attention(q, kc[start:start + clen], vc[start:start + clen], kr, vr, bits, corr, **kw)
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=start, cache_len=clen, correction=corr)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16,
+                                 "case %d: int%d group %s fp8 %s heads %d cap %d live %d window (%d, %d) m %d cur %d corr %d"
+                                 % (case, bits, group, fp8, heads, cap, len(kc), start, clen, m, ncur, corr))
+        checked += 1
+        cache.close()
+    assert checked >= 30
+
+
 @pytest.mark.parametrize("io,group,fp8", [("bf16", None, False), ("bf16", 32, True), ("fp32", None, False)])
 @pytest.mark.parametrize("causal", [False, True])
 def test_grouped_query_heads_and_causal_block(P, io, group, fp8, causal):

@@ -26,6 +26,9 @@ namespace {
 
 #include "kvq_mfma_common.h"
 
+#ifndef KVQ_FREE_LAST_ROWOP
+#define KVQ_FREE_LAST_ROWOP 1
+#endif
 constexpr int kGBuffers = 3;         // a stage is overwritten three stages after it was opened
 constexpr float kPShift = 7.0f;      // f16 probabilities: the row maximum sits at 2^7, overflow at 2^16
 
@@ -36,12 +39,15 @@ __device__ inline uint32_t pk_mul_f16(uint32_t a, uint32_t b)
 __device__ inline uint16_t f16_bits(float f) { return (uint16_t)(pack_f16(f, 0.0f) & 0xffffu); }
 __device__ inline float f16_val(uint16_t b) { return f16_lo((uint32_t)b); }
 
-// Constant-term slots.  Slot s = 11 j + t belongs to group j; slot 11 G is the window mask.
+// Constant-term slots.  Slot s = 11 j + t belongs to group j; slot 11 G is the window mask; slots 11 G + 1
+// and 11 G + 2 carry minus the row's reference maximum (two bf16 pieces on the row side against ones on the
+// key side), so that the accumulators come out relative to the reference and no vector instruction has to
+// subtract it.  The reference is kept equal to the sum of its two pieces.
 //   t = 0..2   key side step_j             x row side -BASE W_j      in three bf16 pieces
 //   t = 3..8   key side (z step)_j, 2 pcs  x row side -S_j           in three pieces (each key piece meets all)
 //   t = 9..10  key side step_j^2           x row side -nu'_j         in two pieces
 template <int G> struct Slots {
-    static constexpr int kCount = 11 * G + 1;
+    static constexpr int kCount = 11 * G + 3;
     static constexpr int kOperands = (kCount + 15) / 16;   // 16-wide MFMAs
 };
 struct Split3 {
@@ -78,6 +84,7 @@ template <int G> __device__ inline uint16_t row_slot(const RowGroup (&r)[G], int
 template <int G> __device__ inline uint16_t key_slot(const KeyGroup (&k)[G], uint16_t bias, int s)
 {
     if (s == 11 * G) return bias;
+    if (s == 11 * G + 1 || s == 11 * G + 2) return 0x3f80u;   // 1.0 against the reference pieces
     if (s > 11 * G) return 0u;
     const int j = s / 11, t = s % 11;
     const KeyGroup &g = k[j];
@@ -279,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
 #pragma unroll
-    for (int c = 0; c < NC; ++c)
+    for (int c = 0; c < NC - KVQ_FREE_LAST_ROWOP; ++c)   // the last operand holds the reference slots and changes with them
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb) asm volatile("" : "+a"(rowop[c][rb]));
 
@@ -303,13 +310,30 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
     float tau[kRB][4] = {};
     bool first = true;
 
+    // Writes the pieces of minus the reference into slots 11 G + 1, 11 G + 2 of the row operands of block rb.
+    auto set_reference_slots = [&](int rb, uint16_t neg_h, uint16_t neg_l) {
+        static_for<2>([&](auto p_) {
+            constexpr int P2 = decltype(p_)::value;
+            constexpr int SL = 11 * G + 1 + P2, C = SL / 16, K = SL % 16, R = (K % 8) / 2;
+            const uint32_t val = P2 == 0 ? neg_h : neg_l;
+            if (hh == K / 8) {
+                const uint32_t old = rowop[C][rb][R];
+                rowop[C][rb][R] = (K % 2) ? ((old & 0x0000ffffu) | (val << 16)) : ((old & 0xffff0000u) | val);
+            }
+        });
+    };
     auto move_reference = [&](float (&e)[kRB][16], const float (&tmax)[kRB]) {
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb) {
             const bool mv = first || tmax[rb] > kRescaleThreshold + kPShift;
-            const float delta = mv ? tmax[rb] - kPShift : 0.0f;
+            // the new reference is the sum of two bf16 pieces: the operand slots hold exactly what is subtracted
+            const float want = m_ref[rb] + (mv ? tmax[rb] - kPShift : 0.0f);
+            const uint16_t r_h = bf16_bits(want);
+            const uint16_t r_l = bf16_bits(want - bf16_val(r_h));
+            const float delta = mv ? (bf16_val(r_h) + bf16_val(r_l)) - m_ref[rb] : 0.0f;
             const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta);
             m_ref[rb] += delta;
+            if (mv) set_reference_slots(rb, (uint16_t)(r_h ^ 0x8000u), (uint16_t)(r_l ^ 0x8000u));
 #pragma unroll
             for (int v = 0; v < 16; ++v) e[rb][v] -= delta;
             l_s[rb] *= alpha;
@@ -339,7 +363,6 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         const int n_stages = (n_tiles + kStageTiles - 1) / kStageTiles;
         const int64_t head_tile0 = (int64_t)head * cv.cap_tiles;
         const int64_t meta0 = head_tile0 * kTileTokens;
-        const int64_t cap_tokens = cv.cap_tiles * kTileTokens;
 
         // ---- loader: global -> registers (prefetch), registers -> LDS (commit, builds every per-key operand)
         constexpr int kCodeVecs = St::kCodeWords / 4;
@@ -349,26 +372,37 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         uint16_t pre_kz[G], pre_vz[G];     // BF16 encodings
         uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1;
+        // Ring arithmetic in 32 bits (the launcher sends caches of 2^30 tiles or more per head elsewhere): the
+        // stage's first physical tile is uniform, a thread adds its tile inside the stage and wraps once more.
+        const int cap = (int)cv.cap_tiles;
+        const int first_off = (int)(cs - t_first * kTileTokens);   // position of cache_start inside its tile
+        const int win_len = (int)a.cache_len;
+        const uint32_t *code_src[kCodeIters];
+        int code_tile[kCodeIters];
+#pragma unroll
+        for (int it = 0; it < kCodeIters; ++it) {
+            const int g = tid + kThreads * it, vec = g % kCodeVecs;
+            code_tile[it] = vec / (16 * WPL);
+            code_src[it] = (g < kCodeVecs ? cv.k_codes : cv.v_codes) + head_tile0 * (64 * WPL) + (vec % (16 * WPL)) * 4;
+        }
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
-            const int64_t tile0 = t_first + (int64_t)stage * kStageTiles;
-            const int64_t phys_tile0 = a.phys_tile_first + (int64_t)stage * kStageTiles;
+            int ring0 = (int)a.phys_tile_first + stage * kStageTiles;   // < 2 cap + 4: n_tiles <= cap + 1
+            ring0 -= ring0 >= cap ? cap : 0;
+            ring0 -= ring0 >= cap ? cap : 0;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
-                const int g = tid + kThreads * it, vec = g % kCodeVecs;
-                int64_t tile = phys_tile0 + vec / (16 * WPL);   // ring: at most two wraps (n_tiles <= cap_tiles + 1)
-                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
-                tile = tile >= cv.cap_tiles ? tile - cv.cap_tiles : tile;
-                tile = tile < cv.cap_tiles ? tile : cv.cap_tiles - 1;   // tiles past the window: any address inside the storage
-                const int64_t word = (head_tile0 + tile) * (64 * WPL) + (vec % (16 * WPL)) * 4;
-                pre_kv[it] = *reinterpret_cast<const u32x4 *>((g < kCodeVecs ? cv.k_codes : cv.v_codes) + word);
+                int tile = ring0 + code_tile[it];
+                tile -= tile >= cap ? cap : 0;    // tiles past the window wrap onto tiles of the storage: masked later
+                tile = tile < cap ? tile : cap - 1;   // (a ring of fewer than four tiles)
+                pre_kv[it] = *reinterpret_cast<const u32x4 *>(code_src[it] + (int64_t)tile * (64 * WPL));
             }
-            int64_t tok = tile0 * kTileTokens + ld_key;
-            pre_in_window = (tok >= cs && tok < ce) ? 1u : 0u;
-            tok = phys_tile0 * kTileTokens + ld_key;
-            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
-            tok = tok >= cap_tokens ? tok - cap_tokens : tok;
-            tok = tok < cap_tokens ? tok : cap_tokens - 1;
+            const int rel = stage * kStageKeys + ld_key - first_off;    // position inside the window
+            pre_in_window = (rel >= 0 && rel < win_len) ? 1u : 0u;
+            int mt = ring0 + (ld_key >> 5);
+            mt -= mt >= cap ? cap : 0;
+            mt = mt < cap ? mt : cap - 1;
+            const int64_t tok = (int64_t)mt * kTileTokens + (ld_key & 31);
             const int64_t gi = (meta0 + tok) * G;
 #pragma unroll
             for (int j = 0; j < G; ++j) {
@@ -567,7 +601,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) e[rb][v] = sn[rb][v] - m_ref[rb];
+                for (int v = 0; v < 16; ++v) e[rb][v] = sn[rb][v];   // already relative to the reference
                 float mx = fmaxf(e[rb][0], e[rb][1]);
 #pragma unroll
                 for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(e[rb][v], e[rb][v + 1]));
@@ -703,7 +737,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 for (int i = 0; i < 8; ++i) vs_cur[i] = vs_nxt[i];
                 constexpr int RB = (B * 4 * kRB) / 16, V0 = (B * 4 * kRB) % 16;
 #pragma unroll
-                for (int v = V0; v < V0 + 4 * kRB; ++v) e[RB][v] = sn[RB][v] - m_ref[RB];
+                for (int v = V0; v < V0 + 4 * kRB; ++v) {
+                    e[RB][v] = sn[RB][v];                  // already relative to the reference
+                    asm volatile("" : "+v"(e[RB][v]));     // copied out of the accumulation register here, not later
+                }
 #pragma unroll
                 for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
                 KVQ_CHUNK_FENCE();

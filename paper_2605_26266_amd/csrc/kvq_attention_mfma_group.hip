@@ -553,11 +553,21 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             return z;
         };
         // tau of tile t from its probabilities: rows 4 hh .. 4 hh + 3 of the result belong to this lane half.
+        // Row 8 of the operand is all ones, so that the same two MFMAs also leave the tile's row sum (of the
+        // rounded probabilities, the ones the output is made of) in register 4 of the lanes of half 0; row 12,
+        // which lands in register 4 of half 1, is zero.  (Rows 8 .. 31 otherwise repeat rows 0 .. 7 and are
+        // not read.)
+        const uint32_t tau_keep = (n == 8 || n == 12) ? 0u : 0xffffffffu;
+        const uint32_t tau_ones = n == 8 ? 0x3c003c00u : 0u;   // f16 1.0 pairs
         auto load_tau_operand = [&](int t, u32x4 (&top)[2]) {
             const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kGBuffers) * St::kWords;
             const uint32_t *src = buf + St::kTau + ((((t & 3) * 2) * 2 + hh) * 8 + (n & 7)) * 4;
             top[0] = *reinterpret_cast<const u32x4 *>(src);
             top[1] = *reinterpret_cast<const u32x4 *>(src + 2 * 8 * 4);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) top[i][j] = (top[i][j] & tau_keep) | tau_ones;
         };
         auto add_tau = [&](const u32x4 (&top)[2], const u32x4 (&pop)[kRB][2]) {
             const u32x4 t0 = top[0], t1 = top[1];
@@ -567,6 +577,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 tt = mfma_f16(t1, pop[rb][1], tt);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) tau[rb][i] += tt[i];
+                l_s[rb] += tt[4];   // half 0: the row sum of the tile; half 1: zero
             }
         };
         // Scores of tile t in log2 units (everything but the reference): constant terms, then high and low
@@ -608,20 +619,17 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 tmax[rb] = max_halves(mx);
             }
         };
-        // p = 2^e as f16 B operands, partial row sums.
+        // p = 2^e as f16 B operands (the row sums come out of the tau MFMAs).
         auto exp_tile = [&](const float (&e)[kRB][16], u32x4 (&pop)[kRB][2]) {
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
-                float lsum = 0.0f;
                 uint32_t pw[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[rb][2 * i]);
                     const float p1 = __builtin_amdgcn_exp2f(e[rb][2 * i + 1]);
-                    lsum += p0 + p1;
                     pw[i] = pack_f16(p0, p1);
                 }
-                l_s[rb] += lsum;
                 pop[rb][0].x = pw[0]; pop[rb][0].y = pw[1]; pop[rb][0].z = pw[2]; pop[rb][0].w = pw[3];
                 pop[rb][1].x = pw[4]; pop[rb][1].y = pw[5]; pop[rb][1].z = pw[6]; pop[rb][1].w = pw[7];
             }
@@ -672,7 +680,6 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
 #pragma unroll
                 for (int c = 1; c < NC; ++c) sn[rb] = mfma_bf16(pf.cop[c], rowop[c][rb], sn[rb]);
             }
-            float lsum[kRB] = {};
             uint32_t pw[kRB][8];
             uint32_t vw[WPL];
             uint32_t vs_cur[8], vs_nxt[8];
@@ -684,7 +691,6 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 for (int i = I0; i < I0 + kRB; ++i) {
                     const float p0 = __builtin_amdgcn_exp2f(e[RB][2 * i]);
                     const float p1 = __builtin_amdgcn_exp2f(e[RB][2 * i + 1]);
-                    lsum[RB] += p0 + p1;
                     pw[RB][i] = pack_f16(p0, p1);
                 }
             };
@@ -714,7 +720,6 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             exp_chunk(IntC<7>{});
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
-                l_s[rb] += lsum[rb];
                 pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
                 pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
             }

@@ -295,8 +295,8 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     // the exact (sinh) correction is a diagnostic mode: vector kernel only
     force_vector = force_vector || correction == 2;
     force_vector = force_vector || d.key_axis == KVQ_KEYS_PER_CHANNEL;   // per-channel keys: vector kernel only
-    // (the matrix-core loaders do their ring arithmetic in 32 bits)
-    force_vector = force_vector || cache_len >= (int64_t(1) << 31) || cache->view.cap_tiles >= (int64_t(1) << 30);
+    // (the matrix-core loaders do their ring arithmetic and their offsets inside a head in 32 bits)
+    force_vector = force_vector || cache_len >= (int64_t(1) << 31) || cache->view.cap_tiles >= (int64_t(1) << 20);
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&
                              d.group_size == d.head_dim;   // one (scale, zero-point) per token, either format
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);

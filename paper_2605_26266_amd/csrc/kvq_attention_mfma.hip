@@ -435,19 +435,18 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1; // one (key, operand half) per thread below 256
         const bool ld_meta = tid < 2 * kStageKeys;
-        // Ring arithmetic in 32 bits (the launcher sends caches of 2^30 tiles or more per head elsewhere): the
+        // Ring arithmetic in 32 bits (the launcher sends caches of 2^20 tiles or more per head elsewhere): the
         // stage's first physical tile is uniform, a thread adds its tile inside the stage and wraps once more.
         const int cap = (int)cv.cap_tiles;
         const int first_off = (int)(cs - t_first * kTileTokens);   // position of cache_start inside its tile
         const int win_len = (int)a.cache_len;
-        const uint32_t *code_src[kCodeIters];
-        int code_tile[kCodeIters];
-#pragma unroll
-        for (int it = 0; it < kCodeIters; ++it) {
-            const int g = tid + kThreads * it, vec = g % kCodeVecs;
-            code_tile[it] = vec / (16 * WPL);
-            code_src[it] = (g < kCodeVecs ? cv.k_codes : cv.v_codes) + head_tile0 * (64 * WPL) + (vec % (16 * WPL)) * 4;
-        }
+        // Addresses are a uniform 64-bit base (head) plus a 32-bit offset per thread, the form a global load
+        // takes with its base in scalar registers: no 64-bit address per thread is kept across the loop.
+        const uint32_t *k_head = cv.k_codes + head_tile0 * (64 * WPL), *v_head = cv.v_codes + head_tile0 * (64 * WPL);
+        const float *m_kscale = cv.k_scale + meta0, *m_knegzero = cv.k_negzero + meta0;
+        const float *m_vscale = cv.v_scale + meta0, *m_vzero = cv.v_zero_off + meta0;
+        const uint8_t *m_kscale8 = cv.k_scale8 + meta0, *m_vscale8 = cv.v_scale8 + meta0;
+        const uint16_t *m_kzero16 = cv.k_zero16 + meta0, *m_vzero16 = cv.v_zero16 + meta0;
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
             int ring0 = (int)a.phys_tile_first + stage * kStageTiles;   // < 2 cap + 4: n_tiles <= cap + 1
@@ -455,10 +454,12 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             ring0 -= ring0 >= cap ? cap : 0;
 #pragma unroll
             for (int it = 0; it < kCodeIters; ++it) {
-                int tile = ring0 + code_tile[it];
+                const int vec = (tid + kThreads * it) % kCodeVecs;   // it < kCodeIters / 2: keys, else values
+                int tile = ring0 + vec / (16 * WPL);
                 tile -= tile >= cap ? cap : 0;    // tiles past the window wrap onto tiles of the storage: masked later
                 tile = tile < cap ? tile : cap - 1;   // (a ring of fewer than four tiles)
-                pre_kv[it] = *reinterpret_cast<const u32x4 *>(code_src[it] + (int64_t)tile * (64 * WPL));
+                const uint32_t word = (uint32_t)tile * (64 * WPL) + (uint32_t)(vec % (16 * WPL)) * 4u;
+                pre_kv[it] = *reinterpret_cast<const u32x4 *>((it < kCodeIters / 2 ? k_head : v_head) + word);
             }
             if (!ld_meta) return;
             const int rel = stage * kStageKeys + ld_key - first_off;    // position inside the window
@@ -466,27 +467,27 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             int mt = ring0 + (ld_key >> 5);
             mt -= mt >= cap ? cap : 0;
             mt = mt < cap ? mt : cap - 1;
-            const int64_t tok = (int64_t)mt * kTileTokens + (ld_key & 31);
+            const uint32_t tok = (uint32_t)mt * kTileTokens + (uint32_t)(ld_key & 31);
             if constexpr (!FP8META) {
                 if (ld_half == 0) {
-                    pre_a = cv.k_negzero[meta0 + tok];
-                    pre_b = cv.k_scale[meta0 + tok];
-                    pre_c = cv.v_scale[meta0 + tok];
+                    pre_a = m_knegzero[tok];
+                    pre_b = m_kscale[tok];
+                    pre_c = m_vscale[tok];
                 } else {
-                    pre_a = cv.k_scale[meta0 + tok];
-                    pre_b = cv.v_scale[meta0 + tok];
-                    pre_c = cv.v_zero_off[meta0 + tok];
+                    pre_a = m_kscale[tok];
+                    pre_b = m_vscale[tok];
+                    pre_c = m_vzero[tok];
                 }
             } else {   // FP8 E4M3 scale, BF16 zero-point, one pair per token
-                const float ks = e4m3_to_float(cv.k_scale8[meta0 + tok]);
+                const float ks = e4m3_to_float(m_kscale8[tok]);
                 if (ld_half == 0) {
-                    pre_a = -(bf16_val(cv.k_zero16[meta0 + tok]) + Unpack<BITS>::kStoredOffset);
+                    pre_a = -(bf16_val(m_kzero16[tok]) + Unpack<BITS>::kStoredOffset);
                     pre_b = ks;
-                    pre_c = e4m3_to_float(cv.v_scale8[meta0 + tok]);
+                    pre_c = e4m3_to_float(m_vscale8[tok]);
                 } else {
                     pre_a = ks;
-                    pre_b = e4m3_to_float(cv.v_scale8[meta0 + tok]);
-                    pre_c = bf16_val(cv.v_zero16[meta0 + tok]) + Unpack<BITS>::kStoredOffset;
+                    pre_b = e4m3_to_float(m_vscale8[tok]);
+                    pre_c = bf16_val(m_vzero16[tok]) + Unpack<BITS>::kStoredOffset;
                 }
             }
         };

@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         uint16_t pre_kz[G], pre_vz[G];     // BF16 encodings
         uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1;
-        // Ring arithmetic in 32 bits (the launcher sends caches of 2^30 tiles or more per head elsewhere): the
+        // Ring arithmetic in 32 bits (the launcher sends caches of 2^20 tiles or more per head elsewhere): the
         // stage's first physical tile is uniform, a thread adds its tile inside the stage and wraps once more.
         const int cap = (int)cv.cap_tiles;
         const int first_off = (int)(cs - t_first * kTileTokens);   // position of cache_start inside its tile

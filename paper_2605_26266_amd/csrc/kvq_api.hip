@@ -292,9 +292,24 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.correction = correction;
     a.out = out;
     a.mass_cached = mass_cached;
+    a.n_key_blocks = 0;
     // the exact (sinh) correction is a diagnostic mode: vector kernel only
     force_vector = force_vector || correction == 2;
-    force_vector = force_vector || d.key_axis == KVQ_KEYS_PER_CHANNEL;   // per-channel keys: vector kernel only
+    if (d.key_axis == KVQ_KEYS_PER_CHANNEL && !force_vector) {
+        // The matrix-core kernel walks the window block by block: list the appended blocks it overlaps.  A window
+        // without cached keys or with more blocks than the list holds goes to the vector kernel.
+        const int64_t w0 = a.cache_start, w1 = a.cache_start + cache_len;
+        int nb = 0;
+        bool fits = cache_len > 0;
+        for (const kvq_block &b : cache->blocks) {
+            const int64_t s0 = b.start > w0 ? b.start : w0, s1 = b.start + b.count < w1 ? b.start + b.count : w1;
+            if (s0 >= s1) continue;
+            if (nb == kvq::kMaxKeyBlocks) { fits = false; break; }
+            a.key_blocks[nb++] = kvq::KeyBlock{(int32_t)b.slot, (int32_t)(s0 - w0), (int32_t)(s1 - w0)};
+        }
+        a.n_key_blocks = nb;
+        force_vector = !fits || nb == 0;
+    }
     // (the matrix-core loaders do their ring arithmetic and their offsets inside a head in 32 bits)
     force_vector = force_vector || cache_len >= (int64_t(1) << 31) || cache->view.cap_tiles >= (int64_t(1) << 20);
     const bool matrix_path = !force_vector && d.io_dtype == KVQ_BF16 && d.head_dim == 128 &&

@@ -97,7 +97,12 @@ template <int BITS> constexpr size_t lds_bytes()
 
 
 // FP8META: the cache holds one FP8 E4M3 scale and one BF16 zero-point per token instead of two floats.
-template <int BITS, bool CORR, bool FP8META>
+// PERCH: keys quantized per channel and appended block (appendix on per-channel quantization).  Inside a block
+// the channel steps go into the query operand, q'_c = q~_c * step_c, after which the block looks like a
+// per-token cache with step 1 and zero-point 0 whose rows carry two constants: Z = sum_c q'_c z_c and the
+// block's correction sigma^2 / 24 * sum_c (q^_c step_c)^2.  The cached keys are therefore processed block by
+// block, the query operands prepared anew for each.
+template <int BITS, bool CORR, bool FP8META, bool PERCH = false>
 __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
 {
     using St = Stage<BITS>;
@@ -418,9 +423,249 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         return over;
     };
 
+    // The query preparation once more, for one block of a per-channel cache (the operands above are replaced):
+    // ch_step, ch_zero are the steps and zero-points of the rotated channels of that block.
+    auto reprepare = [&](const float *ch_step, const float *ch_zero) {
+    if constexpr (PERCH) {
+    {
+        const int prow = tid / kPrepLanes, ppart = tid % kPrepLanes;
+        int64_t row = (int64_t)rblk * kRowsPerBlock + prow;
+        row = row < a.m ? row : a.m - 1;
+        const uint4 *src = reinterpret_cast<const uint4 *>(q_base + row * a.q_stride_token + ppart * kPrepCh);
+        float x[kPrepCh];
+#pragma unroll
+        for (int i = 0; i < kPrepCh / 8; ++i) {
+            const uint4 w = src[i];
+            const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[8 * i + 2 * j] = __uint_as_float(ws[j] << 16);
+                x[8 * i + 2 * j + 1] = __uint_as_float(ws[j] & 0xffff0000u);
+            }
+        }
+        float nu = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kPrepCh; ++i) nu = fmaf(x[i], x[i], nu);
+        // Randomised rotation: the channel signs come before the Hadamard matrix.
+        if (has_signs(a.cv))
+#pragma unroll
+        for (int w = 0; w < kPrepCh / 32; ++w) {
+            const uint32_t sg = sign_bits_from(a.cv, ppart * kPrepCh + 32 * w);
+#pragma unroll
+            for (int i = 0; i < 32; ++i) x[32 * w + i] = flip_sign(x[32 * w + i], sg >> i);
+        }
+#pragma unroll
+        for (int h = 1; h < kPrepCh; h <<= 1) {
+#pragma unroll
+            for (int i = 0; i < kPrepCh; ++i) {
+                if ((i & h) == 0) {
+                    const float p = x[i], q2 = x[i + h];
+                    x[i] = p + q2;
+                    x[i + h] = p - q2;
+                }
+            }
+        }
+        if constexpr (kPrepLanes == 2) {   // last butterfly stage: between the two lanes of the row
+            nu += __shfl_xor(nu, 1);
+#pragma unroll
+            for (int i = 0; i < kPrepCh; ++i) {
+                const float other = __shfl_xor(x[i], 1);
+                x[i] = ppart ? other - x[i] : x[i] + other;
+            }
+        }
+        if constexpr (PERCH) {   // q^_c step_c: the block's correction, then the operand
+            nu = 0.0f;
+#pragma unroll
+            for (int i = 0; i < kPrepCh; ++i) {
+                x[i] *= ch_step[i];
+                const float t = x[i] * 0.088388347648318f;
+                nu = fmaf(t, t, nu);
+            }
+        }
+        // Channel c of the operand carries 4^g(c) (the inverse of the weight its key codes are unpacked with).
+        const float cq = c_log * 0.088388347648318f;
+#pragma unroll
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (float)(1 << (2 * key_channel_class<BITS>(i)));
+        // The staging rows hold the high parts first (read into registers below), then the low parts,
+        // which stay in LDS for the whole cached-key loop.
+        uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
+#pragma unroll
+        for (int i = 0; i < kPrepCh / 8; ++i) {
+            u32x4 w;
+            w.x = pack_f16(x[8 * i], x[8 * i + 1]); w.y = pack_f16(x[8 * i + 2], x[8 * i + 3]);
+            w.z = pack_f16(x[8 * i + 4], x[8 * i + 5]); w.w = pack_f16(x[8 * i + 6], x[8 * i + 7]);
+            *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+        }
+        __syncthreads();
+        const uint32_t *hsrc = q_stage + (wave * kRowsPerWave + n) * kQRowWords + 4 * hh;
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                qop[rb][s] = *reinterpret_cast<const u32x4 *>(hsrc + 32 * rb * kQRowWords + 8 * s);
+        __syncthreads();
+        float ssum = 0.0f, ssum_w = 0.0f;   // sum of q~ (true scale), sum of the weighted operand values
+        if constexpr (kLoFp8) {
+            static_assert(!kLoFp8 || kPrepLanes == 1, "one lane prepares a whole row");
+            // Low parts at true scale (the weight 4^g of the high operand taken out again: exact), their
+            // largest magnitude, and from it the row's power-of-two scale: the largest low part lands in
+            // [128, 256), inside the E4M3 range.
+            float lo_t[kPrepCh], mx = 0.0f;
+#pragma unroll
+            for (int c = 0; c < kPrepCh; c += 2) {
+                const uint32_t hi = pack_f16(x[c], x[c + 1]);
+                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(c)));   // both channels share a class
+                lo_t[c] = (x[c] - f16_lo(hi)) * wgt;
+                lo_t[c + 1] = (x[c + 1] - f16_hi(hi)) * wgt;
+                mx = fmaxf(mx, fmaxf(fabsf(lo_t[c]), fabsf(lo_t[c + 1])));
+                ssum_w += f16_lo(hi) + f16_hi(hi);
+                if constexpr (PERCH) ssum += (f16_lo(hi) * ch_zero[c] + f16_hi(hi) * ch_zero[c + 1]) * wgt;
+                else ssum += (f16_lo(hi) + f16_hi(hi)) * wgt;
+            }
+            const int ex = mx > 0.0f ? (int)((__float_as_uint(mx) >> 23) & 0xffu) - 127 - 7 : 0;   // floor(log2 mx) - 7
+            const float down = __uint_as_float((uint32_t)(127 - ex) << 23), up = __uint_as_float((uint32_t)(127 + ex) << 23);
+            // Operand order: MFMA j (channels of key words 2 j, 2 j + 1), lane half hh, register r8, byte b hold
+            // the channel whose code the key unpacking puts into the same byte.
+#pragma unroll
+            for (int w = 0; w < 32; ++w) {
+                const int j = w >> 4, hw = (w >> 3) & 1, r8 = w & 7;
+                float v[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int slab = 2 * (2 * j + (r8 >> 2)) + (b & 1);
+                    v[b] = lo_t[16 * slab + 8 * hw + 2 * (r8 & 3) + (b >> 1)] * down;
+                }
+                int word = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], 0, false);
+                word = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], word, true);
+                dst[w] = (uint32_t)word;
+                float dec = 0.0f, dec_z = 0.0f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const float d8 = e4m3_to_float((uint8_t)((uint32_t)word >> (8 * b)));
+                    dec += d8;
+                    if constexpr (PERCH) {
+                        const int slab = 2 * (2 * j + (r8 >> 2)) + (b & 1);
+                        dec_z = fmaf(d8, ch_zero[16 * slab + 8 * hw + 2 * (r8 & 3) + (b >> 1)], dec_z);
+                    }
+                }
+                ssum += (PERCH ? dec_z : dec) * up;      // the sums follow the operands the MFMAs will see
+                ssum_w += 2.0f * (dec * up);   // FP8 key values are 8 + code, twice the BASE the constant term takes off
+            }
+            row_scal[4 * prow + 3] = __int_as_float(127 + ex);
+        } else {
+#pragma unroll
+        for (int i = 0; i < kPrepCh / 8; ++i) {
+            uint32_t lo[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float v0 = x[8 * i + 2 * j], v1 = x[8 * i + 2 * j + 1];
+                const uint32_t hi = pack_f16(v0, v1);
+                const float h0 = f16_lo(hi), h1 = f16_hi(hi);
+                lo[j] = pack_f16(v0 - h0, v1 - h1);
+#if KVQ_Q_LOW_PART
+                const float pair = (h0 + f16_lo(lo[j])) + (h1 + f16_hi(lo[j]));   // both channels share a class
+#else
+                const float pair = h0 + h1;
+#endif
+                ssum_w += pair;
+                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(8 * i + 2 * j)));
+#if KVQ_Q_LOW_PART
+                if constexpr (PERCH)
+                    ssum += ((h0 + f16_lo(lo[j])) * ch_zero[8 * i + 2 * j] + (h1 + f16_hi(lo[j])) * ch_zero[8 * i + 2 * j + 1]) * wgt;
+                else
+#endif
+                ssum += pair * wgt;
+            }
+            u32x4 w;
+            w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
+            *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+        }
+        }
+        if constexpr (kPrepLanes == 2) {
+            ssum += __shfl_xor(ssum, 1);
+            ssum_w += __shfl_xor(ssum_w, 1);
+        }
+        if (ppart == 0) {
+            row_scal[4 * prow] = ssum;
+            row_scal[4 * prow + 1] = ssum_w;
+            row_scal[4 * prow + 2] = CORR ? -a.softmax_scale * a.softmax_scale * kLog2e * nu * (1.0f / 24.0f) : 0.0f;
+        }
+    }
+    __syncthreads();
+    // B operand of the constant-term MFMA, per 32-row block.  The raw score is sum_c (q~_c 4^g) (BASE +
+    // 4^-g code_c) = q~ . code + BASE * W with W the sum of the weighted operand values, so what has to
+    // come off is z * S + BASE * W (S = sum_c q~_c).  Lane half 0 multiplies the key's -z pieces and the
+    // mask bias, lane half 1 the key's scale pieces and the constant -BASE:
+    //   hh = 0: [S_h, S_m, S_l, S_h, S_m, S_l, 1, 0]     S in three bf16 pieces
+    //   hh = 1: [N_h, N_l, N_h, N_l, W_h, W_m, W_l, 0]   N = -nu' in two pieces, W in three
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) {
+        const float *rs = row_scal + 4 * (wave * kRowsPerWave + 32 * rb + n);
+        const float ssum = rs[0], wsum = rs[1], nnu = rs[2];
+        const uint16_t s_h = bf16_bits(ssum);
+        const float r1 = ssum - bf16_val(s_h);
+        const uint16_t s_m = bf16_bits(r1);
+        const uint16_t s_l = bf16_bits(r1 - bf16_val(s_m));
+        const uint16_t w_h = bf16_bits(wsum);
+        const float r2 = wsum - bf16_val(w_h);
+        const uint16_t w_m = bf16_bits(r2);
+        const uint16_t w_l = bf16_bits(r2 - bf16_val(w_m));
+        const uint16_t n_h = bf16_bits(nnu);
+        const uint16_t n_l = bf16_bits(nnu - bf16_val(n_h));
+        const uint32_t one = 0x3f80u;
+        u32x4 w0, w1;
+        w0.x = s_h | ((uint32_t)s_m << 16); w0.y = s_l | ((uint32_t)s_h << 16);
+        w0.z = s_m | ((uint32_t)s_l << 16); w0.w = one | (one << 16);
+        w1.x = n_h | ((uint32_t)n_l << 16); w1.y = w1.x;
+        w1.z = w_h | ((uint32_t)w_m << 16); w1.w = w_l | (one << 16);
+        rowop[rb] = hh ? w1 : w0;
+    }
+    // The 64 registers of query operands live in accumulation registers (MFMA reads them from there
+    // directly), which leaves the vector registers to the score tile in flight.
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
+
+    if constexpr (kLoFp8) {
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+            const uint32_t *src = q_stage + (wave * kRowsPerWave + 32 * rb + n) * kQRowWords + 8 * hh;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const u32x4 w0 = *reinterpret_cast<const u32x4 *>(src + 16 * j);
+                const u32x4 w1 = *reinterpret_cast<const u32x4 *>(src + 16 * j + 4);
+                lo8[rb][j] = i32x8{(int)w0.x, (int)w0.y, (int)w0.z, (int)w0.w, (int)w1.x, (int)w1.y, (int)w1.z, (int)w1.w};
+                asm volatile("" : "+a"(lo8[rb][j]));
+            }
+            lo_scale[rb] = __float_as_int(row_scal[4 * (wave * kRowsPerWave + 32 * rb + n) + 3]);
+        }
+    }
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int s = 0; s < kLoRes; ++s) {
+            lo_res[rb][s] = *reinterpret_cast<const u32x4 *>(q_stage + lo_off + 32 * rb * kQRowWords + 8 * s);
+            asm volatile("" : "+a"(lo_res[rb][s]));
+        }
+    }
+    };
+
     // ---------------------------------------------------------------------- cached keys ----
     if (a.cache_len > 0) {
-        const int64_t cs = a.cache_start, ce = a.cache_start + a.cache_len;
+        // Per-channel caches: one pass per key block of the window, each with its own query operands.
+        for (int bi = 0; bi < (PERCH ? a.n_key_blocks : 1); ++bi) {
+        int64_t cs = a.cache_start, ce = a.cache_start + a.cache_len;
+        int phys_first = (int)a.phys_tile_first;
+        if constexpr (PERCH) {
+            const KeyBlock kb = a.key_blocks[bi];
+            cs = a.cache_start + kb.start;
+            ce = a.cache_start + kb.end;
+            phys_first = (int)((a.phys_tile_first + (cs / kTileTokens - a.cache_start / kTileTokens)) % cv.cap_tiles);
+            __syncthreads();   // every wave has left the previous block's tiles and staging rows
+            reprepare(cv.kc_scale + ((int64_t)kb.slot * cv.num_heads + head) * D,
+                      cv.kc_zero + ((int64_t)kb.slot * cv.num_heads + head) * D);
+        }
         const int64_t t_first = cs / kTileTokens, t_last = (ce - 1) / kTileTokens;
         const int n_tiles = (int)(t_last - t_first + 1);
         const int n_stages = (n_tiles + kStageTiles - 1) / kStageTiles;
@@ -439,7 +684,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // stage's first physical tile is uniform, a thread adds its tile inside the stage and wraps once more.
         const int cap = (int)cv.cap_tiles;
         const int first_off = (int)(cs - t_first * kTileTokens);   // position of cache_start inside its tile
-        const int win_len = (int)a.cache_len;
+        const int win_len = (int)(ce - cs);
         // Addresses are a uniform 64-bit base (head) plus a 32-bit offset per thread, the form a global load
         // takes with its base in scalar registers: no 64-bit address per thread is kept across the loop.
         const uint32_t *k_head = cv.k_codes + head_tile0 * (64 * WPL), *v_head = cv.v_codes + head_tile0 * (64 * WPL);
@@ -449,7 +694,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const uint16_t *m_kzero16 = cv.k_zero16 + meta0, *m_vzero16 = cv.v_zero16 + meta0;
         auto prefetch = [&](int stage) {
             if (stage >= n_stages) return;
-            int ring0 = (int)a.phys_tile_first + stage * kStageTiles;   // < 2 cap + 4: n_tiles <= cap + 1
+            int ring0 = phys_first + stage * kStageTiles;   // < 2 cap + 4: n_tiles <= cap + 1
             ring0 -= ring0 >= cap ? cap : 0;
             ring0 -= ring0 >= cap ? cap : 0;
 #pragma unroll
@@ -468,7 +713,17 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             mt -= mt >= cap ? cap : 0;
             mt = mt < cap ? mt : cap - 1;
             const uint32_t tok = (uint32_t)mt * kTileTokens + (uint32_t)(ld_key & 31);
-            if constexpr (!FP8META) {
+            if constexpr (PERCH) {   // keys: step 1, the row constant Z meets -1 where a zero-point would stand
+                if (ld_half == 0) {
+                    pre_a = -1.0f - Unpack<BITS>::kStoredOffset;
+                    pre_b = 1.0f;
+                    pre_c = m_vscale[tok];
+                } else {
+                    pre_a = 1.0f;
+                    pre_b = m_vscale[tok];
+                    pre_c = m_vzero[tok];
+                }
+            } else if constexpr (!FP8META) {
                 if (ld_half == 0) {
                     pre_a = m_knegzero[tok];
                     pre_b = m_kscale[tok];
@@ -900,6 +1155,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
         }
 
+        }   // key blocks
+
         // ---- leave the rotated basis: O <- Hn^T (O_rot - tau 1).  Channel index of register
         // (b, v) in lane half hh: c = 32 b + 8 (v >> 2) + 4 hh + (v & 3).
 #pragma unroll
@@ -976,10 +1233,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     }
 }
 
-template <int BITS, bool CORR, bool FP8META> hipError_t launch(const AttentionArgs &a, hipStream_t stream)
+template <int BITS, bool CORR, bool FP8META, bool PERCH = false> hipError_t launch(const AttentionArgs &a, hipStream_t stream)
 {
     static bool configured = false;  // per instantiation; the attribute is a property of the kernel
-    const void *fn = reinterpret_cast<const void *>(&attention_mfma_kernel<BITS, CORR, FP8META>);
+    const void *fn = reinterpret_cast<const void *>(&attention_mfma_kernel<BITS, CORR, FP8META, PERCH>);
     if (!configured) {
         const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<BITS>());
         if (e != hipSuccess) return e;
@@ -988,7 +1245,7 @@ template <int BITS, bool CORR, bool FP8META> hipError_t launch(const AttentionAr
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR, FP8META>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
+    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR, FP8META, PERCH>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
                        a, row_blocks);
     return hipGetLastError();
 }
@@ -1001,6 +1258,11 @@ hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream)
     if (a.cv.meta_format != KVQ_META_FP32 && a.cv.group_size != D) return hipErrorInvalidValue;
     if (a.cache_len > (int64_t)0x3fffffff * kTileTokens) return hipErrorInvalidValue;
     const bool fp8 = a.cv.meta_format == KVQ_META_FP8_BF16;
+    if (a.cv.key_axis == KVQ_KEYS_PER_CHANNEL) {   // the caller has listed the key blocks of the window
+        if (fp8 || a.n_key_blocks < 1 || a.n_key_blocks > kMaxKeyBlocks || a.cache_len < 1) return hipErrorInvalidValue;
+        if (a.cv.bits == 2) return a.correction ? launch<2, true, false, true>(a, stream) : launch<2, false, false, true>(a, stream);
+        return a.correction ? launch<4, true, false, true>(a, stream) : launch<4, false, false, true>(a, stream);
+    }
     if (a.cv.bits == 2 && !fp8) return a.correction ? launch<2, true, false>(a, stream) : launch<2, false, false>(a, stream);
     if (a.cv.bits == 4 && !fp8) return a.correction ? launch<4, true, false>(a, stream) : launch<4, false, false>(a, stream);
     if (a.cv.bits == 2 && fp8) return a.correction ? launch<2, true, true>(a, stream) : launch<2, false, true>(a, stream);

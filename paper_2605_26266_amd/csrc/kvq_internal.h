@@ -140,6 +140,13 @@ hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream);
 
+// One appended block of a KVQ_KEYS_PER_CHANNEL cache inside the attended window: its parameter slot and its
+// token range relative to cache_start.
+struct KeyBlock {
+    int32_t slot, start, end;
+};
+constexpr int kMaxKeyBlocks = 40;   // more blocks than this in one window: vector kernel
+
 struct AttentionArgs {
     CacheView cv;
     int64_t cache_start, cache_len;   // logical token positions (the storage is a ring of cap_tiles tiles)
@@ -153,6 +160,8 @@ struct AttentionArgs {
     int correction;
     void *out;
     float *mass_cached;
+    int32_t n_key_blocks;                 // matrix-core path of per-channel caches only
+    KeyBlock key_blocks[kMaxKeyBlocks];
 };
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream);

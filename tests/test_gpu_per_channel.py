@@ -53,8 +53,10 @@ def test_per_channel_keys(P, name, io, bits):
     tol = P.TOL_OUT_BF16 if io == "bf16" else P.TOL_OUT_FP32
     for correction in (0, 1, 2):
         ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, correction, key_blocks=blocks)
-        out, mass = P.run_gpu_attention(cache, q, kr, vr, io, correction=correction)
-        P.assert_attention_close(out, mass, ref, mass_ref, tol, "per-channel keys, correction %d" % correction)
+        # default dispatch (BF16, d = 128, Taylor or no correction: matrix cores, one pass per key block) and the vector kernel
+        for fp32_kernel in (False, True):
+            out, mass = P.run_gpu_attention(cache, q, kr, vr, io, correction=correction, fp32_kernel=fp32_kernel)
+            P.assert_attention_close(out, mass, ref, mass_ref, tol, "per-channel keys, correction %d" % correction)
     # a window that starts inside the first block and ends inside the third
     s0 = 150 if blocks[0] > 150 else 10
     ln = sum(blocks[:2]) + 20 - s0
@@ -70,6 +72,40 @@ def test_per_channel_keys(P, name, io, bits):
     ref = np.stack([r[0] for r in refs], axis=1)
     mass_ref = np.stack([r[1] for r in refs])
     P.assert_attention_close(out, mass, ref, mass_ref, tol, "per-channel keys, window")
+
+
+def test_per_channel_keys_many_tiles(P):
+    """Five blocks of 1000 tokens (none of them a whole number of tiles), 300 query rows, outlier channels:
+    the block-by-block matrix-core path over several stages per block, with a window that cuts two blocks."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, nblk, blen = 2, 5, 1000
+    cache = P.make_cache(w, nblk * blen + 24, heads=heads, per_channel_keys=True)
+    ks, vs = [], []
+    for i in range(nblk):
+        k, v = wl.chunk_kv(w, i, heads=range(heads), n_tokens=blen)
+        B.kvq_quantize_append(cache, P.to_dev(k, "bf16"), P.to_dev(v, "bf16"))
+        ks.append(k); vs.append(v)
+    kc, vc = np.concatenate(ks), np.concatenate(vs)
+    q = wl.chunk_q(w, heads=range(heads))[:300]
+    kr, vr = wl.chunk_kv(w, 9, heads=range(heads), n_tokens=500)
+    for correction in (1, 0):
+        ref, mass_ref, qds = oracle.chunk_attention(q, kc, vc, kr, vr, 2, correction, key_blocks=[blen] * nblk)
+        if correction == 1:
+            full = qds
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", correction=correction)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "per-channel, 5 x 1000 tokens, correction %d" % correction)
+    s0, ln = 700, 2900                                   # from inside block 0 to inside block 3
+    refs = []
+    for h in range(heads):
+        qd = full[h]
+        khat = oracle.dequantize(qd["k_codes"][s0:s0 + ln], qd["k_scale"][s0:s0 + ln], qd["k_zero"][s0:s0 + ln])
+        vhat = oracle.dequantize(qd["v_codes"][s0:s0 + ln], qd["v_scale"][s0:s0 + ln], qd["v_zero"][s0:s0 + ln])
+        refs.append(oracle.attention(q[:, h, :], khat, qd["k_scale"][s0:s0 + ln], vhat, kr[:, h, :], vr[:, h, :]))
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", cache_start=s0, cache_len=ln)
+    P.assert_attention_close(out, mass, np.stack([r[0] for r in refs], axis=1), np.stack([r[1] for r in refs]),
+                             P.TOL_OUT_BF16, "per-channel, window over four blocks")
 
 
 def test_per_channel_ring_and_block_limit(P):

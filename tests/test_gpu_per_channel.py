@@ -108,6 +108,38 @@ def test_per_channel_keys_many_tiles(P):
                              P.TOL_OUT_BF16, "per-channel, window over four blocks")
 
 
+def test_per_channel_partly_evicted_block_and_grouped_heads(P):
+    """A block that has lost its first tokens keeps the parameters of the whole block; grouped query heads and
+    the causal current block work on the block-by-block path as on the others."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"]
+    heads, blocks = 2, [100, 100, 60]
+    cache = P.make_cache(w, 288, heads=heads, per_channel_keys=True)
+    ks, vs = [], []
+    for i, n in enumerate(blocks):
+        k, v = wl.chunk_kv(w, i, heads=range(heads), n_tokens=n)
+        B.kvq_quantize_append(cache, P.to_dev(k, "bf16"), P.to_dev(v, "bf16"))
+        ks.append(k); vs.append(v)
+    kc, vc = np.concatenate(ks), np.concatenate(vs)
+    B.kvq_cache_evict(cache, 32)
+    q4 = wl.chunk_q(w, heads=range(2 * heads))[:64]               # two query heads per key/value head
+    kr, vr = wl.chunk_kv(w, 9, heads=range(heads), n_tokens=64)
+    full = oracle.chunk_attention(q4[:, :heads], kc, vc, kr, vr, 2, 1, key_blocks=blocks)[2]
+    for causal in (False, True):
+        refs = []
+        for qh in range(2 * heads):
+            qd = full[qh // 2]
+            khat = oracle.dequantize(qd["k_codes"][32:], qd["k_scale"][32:], qd["k_zero"][32:])
+            vhat = oracle.dequantize(qd["v_codes"][32:], qd["v_scale"][32:], qd["v_zero"][32:])
+            refs.append(oracle.attention(q4[:, qh, :], khat, qd["k_scale"][32:], vhat, kr[:, qh // 2, :], vr[:, qh // 2, :],
+                                         causal=causal))
+        ref, mass_ref = np.stack([r[0] for r in refs], axis=1), np.stack([r[1] for r in refs])
+        out, mass = P.run_gpu_attention(cache, q4, kr, vr, "bf16", causal=causal)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "per-channel, evicted head of a block, causal %s" % causal,
+                                 mass_floor=1e-4 if causal else None)
+
+
 def test_per_channel_ring_and_block_limit(P):
     """Blocks are evicted with their tokens; slots are reused; more live blocks than the storage has slots
     for is refused."""

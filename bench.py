@@ -29,8 +29,8 @@ MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/f16 matrix peak
 HBM_PEAK_GBS = 8000.0
 # HBM bytes of one attention launch on the Large workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
 # this program scaled by the same counters on a plain 1 GiB elementwise kernel (--calibration-copy):
-# 224,638 KiB x 2.000 + 53,762 KiB x 1.000 (profiles/attention_mfma_large_int2_counters.md).
-ATTENTION_TRAFFIC_BYTES_LARGE = 515.1e6
+# 223,212 KiB x 2.000 + 52,996 KiB x 1.000 (profiles/attention_mfma_large_int2_counters.md).
+ATTENTION_TRAFFIC_BYTES_LARGE = 511.4e6
 
 
 def parse():
@@ -146,7 +146,7 @@ def run_stream(args, torch, B, wl):
         "per_chunk_latency_ms": [float(a + b) for a, b in zip(t_q, t_a)],
         "attention_tflops": att_tf,
         "pct_mfma_peak": 100.0 * att_tf / MFMA_PEAK_TFLOPS,
-        "roofline": {"kernel": "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false"), "bound": "mfma", "achieved": att_tf,
+        "roofline": {"kernel": "attention_mfma_kernel<2, true, %s, false>" % ("true" if args.meta == "fp8" else "false"), "bound": "mfma", "achieved": att_tf,
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": att_tf / MFMA_PEAK_TFLOPS, "traffic": None},
     }
 
@@ -273,7 +273,7 @@ def main():
         "attention_ms_uncorrected": float(t_off),
         "roofline": {
             "kernel": ("attention_mfma_group_kernel<2, true, %d>" % n_groups if args.group else
-                       "attention_mfma_kernel<2, true, %s>" % ("true" if args.meta == "fp8" else "false")),
+                       "attention_mfma_kernel<2, true, %s, false>" % ("true" if args.meta == "fp8" else "false")),
             "bound": "mfma",
             "achieved": att_tflops,
             "peak": MFMA_PEAK_TFLOPS,

@@ -1,4 +1,5 @@
-// Matrix-core chunk attention for gfx950: BF16 I/O, head_dim 128, 2- or 4-bit cache.
+// Matrix-core chunk attention for gfx950: BF16 I/O, head_dim 128, 2- or 4-bit cache with one (scale, zero-point)
+// per token (fp32 or FP8/BF16 metadata) or with per-channel keys (see PERCH below).
 //
 // Work split.  One workgroup = 4 wavefronts = 256 query rows of one head; each wavefront owns
 // 64 rows (two 32-row blocks) for the whole key loop, so the waves only meet at one barrier per
@@ -16,7 +17,8 @@
 // and a shift per one to three registers: the code lands in mantissa bits of a 16-bit float whose
 // exponent makes the value BASE + weight * code (see "Unpacking" below).  Key codes and the rotated
 // query use f16 (same MFMA rate as bf16, three more significant bits; codes are exact either way) and
-// the query is carried as a high + low f16 pair; value codes and probabilities use bf16 (its range is
+// the query is carried as an f16 high part plus a low part (FP8 for 2-bit caches, f16 for 4-bit, see the
+// switches below); value codes and probabilities use bf16 (its range is
 // needed for p * value-scale).  Per-token scale and zero-point never touch the operands: with one
 // (scale, zero) per token
 //     s_mi = scale_i * ( q~_m . (BASE + code_i)  -  z_i * sum_c q~_mc  -  BASE * W_m  -  scale_i * nu'_m )
@@ -45,8 +47,8 @@
 // just scales numerator and denominator alike); that rare case leaves the fast loop, rescales, and
 // re-enters, which keeps the accumulators pinned in their registers inside the loop.
 //
-// Current keys/values (unquantized block).  K rows are read straight into A operands; V tiles are
-// transposed through LDS (token-major operands); scores get no correction.
+// Current keys/values (unquantized block, kvq_mfma_current_phase.inc).  K rows are staged through LDS one tile
+// ahead, V tiles are transposed through LDS (token-major operands); scores get no correction.
 #include "kvq_internal.h"
 
 // 1: the rotated query enters the score MFMAs as an f16 high part plus an f16 low part (two MFMAs per

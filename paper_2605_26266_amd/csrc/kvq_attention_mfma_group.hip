@@ -21,6 +21,8 @@
 //     instead of vector dot products.
 #include "kvq_internal.h"
 
+#include <type_traits>
+
 namespace kvq {
 namespace {
 
@@ -368,8 +370,12 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         constexpr int kCodeVecs = St::kCodeWords / 4;
         constexpr int kCodeIters = 2 * kCodeVecs / kThreads;
         u32x4 pre_kv[kCodeIters];
-        uint8_t pre_ks[G], pre_vs[G];      // E4M3 encodings
-        uint16_t pre_kz[G], pre_vz[G];     // BF16 encodings
+        // The G E4M3 scales and G BF16 zero-points of a token are fetched as whole words and only taken apart when
+        // the stage is committed: unpacking them here would make the wave wait for the loads it has just issued.
+        using ScaleWord = typename std::conditional<G == 4, uint32_t, uint16_t>::type;   // G bytes
+        using ZeroWord = typename std::conditional<G == 4, uint64_t, uint32_t>::type;    // G half-words
+        ScaleWord raw_ks = 0, raw_vs = 0;
+        ZeroWord raw_kz = 0, raw_vz = 0;
         uint32_t pre_in_window = 0u;   // a vector register, not a lane mask: it lives across the loop's branches
         const int ld_key = tid & 127, ld_half = (tid >> 7) & 1;
         // Ring arithmetic in 32 bits (the launcher sends caches of 2^20 tiles or more per head elsewhere): the
@@ -404,17 +410,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             mt = mt < cap ? mt : cap - 1;
             const int64_t tok = (int64_t)mt * kTileTokens + (ld_key & 31);
             const int64_t gi = (meta0 + tok) * G;
-#pragma unroll
-            for (int j = 0; j < G; ++j) {
-                pre_ks[j] = cv.k_scale8[gi + j];
-                pre_kz[j] = cv.k_zero16[gi + j];
-            }
+            raw_ks = *reinterpret_cast<const ScaleWord *>(cv.k_scale8 + gi);   // gi is a multiple of G: aligned
+            raw_kz = *reinterpret_cast<const ZeroWord *>(cv.k_zero16 + gi);
             if (ld_half == 1) {
-#pragma unroll
-                for (int j = 0; j < G; ++j) {
-                    pre_vs[j] = cv.v_scale8[gi + j];
-                    pre_vz[j] = cv.v_zero16[gi + j];
-                }
+                raw_vs = *reinterpret_cast<const ScaleWord *>(cv.v_scale8 + gi);
+                raw_vz = *reinterpret_cast<const ZeroWord *>(cv.v_zero16 + gi);
             }
         };
         auto commit = [&](int stage) {
@@ -432,8 +432,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             uint32_t ks_pair[G];
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                const float step = pre_valid ? e4m3_to_float(pre_ks[j]) : 0.0f;
-                const float zs = step * bf16_val(pre_kz[j]);   // 4 x 8 significant bits: exact
+                const float step = pre_valid ? e4m3_to_float((uint8_t)(raw_ks >> (8 * j))) : 0.0f;
+                const float zs = step * bf16_val((uint16_t)(raw_kz >> (16 * j)));   // 4 x 8 significant bits: exact
                 kg[j].step = bf16_bits(step);
                 kg[j].step2 = bf16_bits(step * step);
                 kg[j].zs_h = bf16_bits(zs);
@@ -469,13 +469,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 uint16_t *tau16 = reinterpret_cast<uint16_t *>(buf + St::kTau);
 #pragma unroll
                 for (int j = 0; j < G; ++j) {
-                    const float step = pre_valid ? e4m3_to_float(pre_vs[j]) : 0.0f;
+                    const float step = pre_valid ? e4m3_to_float((uint8_t)(raw_vs >> (8 * j))) : 0.0f;
                     const uint16_t sw = f16_bits(ldexpf(step, g2));   // step * 4^g, the inverse weight of the codes
 #pragma unroll
                     for (int b = j * kBlocksPerGroup; b < (j + 1) * kBlocksPerGroup; ++b)
                         vs16[(((tl * 4 + b) * 2 + th) * 8 + (v >> 1)) * 2 + (v & 1)] = sw;
                     // tau multiplier: what the operand holds for code = z, i.e. step * (BASE 4^g + z)
-                    const float zz = step * (ldexpf(kBase, g2) + bf16_val(pre_vz[j]));
+                    const float zz = step * (ldexpf(kBase, g2) + bf16_val((uint16_t)(raw_vz >> (16 * j))));
                     const uint16_t z_h = f16_bits(zz);
                     const uint16_t z_l = f16_bits(zz - f16_val(z_h));
                     const int sl = v >> 3, i = v & 7;

@@ -735,16 +735,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     pre_b = m_vscale[tok];
                     pre_c = m_vzero[tok];
                 }
-            } else {   // FP8 E4M3 scale, BF16 zero-point, one pair per token
-                const float ks = e4m3_to_float(m_kscale8[tok]);
+            } else {   // FP8 E4M3 scale, BF16 zero-point, one pair per token: the raw encodings, decoded at the commit
+                       // (decoding here would make the wave wait for the loads it has just issued)
+                // (the aligned words that hold the token's byte / half-word: plain dword loads, like the fp32 format)
+                const float *w_ks = reinterpret_cast<const float *>(m_kscale8), *w_vs = reinterpret_cast<const float *>(m_vscale8);
+                const float *w_kz = reinterpret_cast<const float *>(m_kzero16), *w_vz = reinterpret_cast<const float *>(m_vzero16);
                 if (ld_half == 0) {
-                    pre_a = -(bf16_val(m_kzero16[tok]) + Unpack<BITS>::kStoredOffset);
-                    pre_b = ks;
-                    pre_c = e4m3_to_float(m_vscale8[tok]);
+                    pre_a = w_kz[tok >> 1];
+                    pre_b = w_ks[tok >> 2];
+                    pre_c = w_vs[tok >> 2];
                 } else {
-                    pre_a = ks;
-                    pre_b = e4m3_to_float(m_vscale8[tok]);
-                    pre_c = bf16_val(m_vzero16[tok]) + Unpack<BITS>::kStoredOffset;
+                    pre_a = w_ks[tok >> 2];
+                    pre_b = w_vs[tok >> 2];
+                    pre_c = w_vz[tok >> 1];
                 }
             }
         };
@@ -768,6 +771,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             // Scales are clamped away from zero (an all-zero row has scale 0): such a key scores 0 and its
             // value contributes 2^-64 p, as good as the exact 0.
             const int g2 = 2 * value_register_class<BITS>(slot & 15);
+            if constexpr (FP8META) {   // decode what the prefetch brought
+                const uint32_t ra = __float_as_uint(pre_a), rb = __float_as_uint(pre_b), rc = __float_as_uint(pre_c);
+                const int sb = 8 * (ld_key & 3), sh = 16 * (ld_key & 1);   // the token's byte / half-word inside its word
+                if (ld_half == 0) {
+                    pre_a = -(bf16_val((uint16_t)(ra >> sh)) + Unpack<BITS>::kStoredOffset);
+                    pre_b = e4m3_to_float((uint8_t)(rb >> sb));
+                    pre_c = e4m3_to_float((uint8_t)(rc >> sb));
+                } else {
+                    pre_a = e4m3_to_float((uint8_t)(ra >> sb));
+                    pre_b = e4m3_to_float((uint8_t)(rb >> sb));
+                    pre_c = bf16_val((uint16_t)(rc >> sh)) + Unpack<BITS>::kStoredOffset;
+                }
+            }
             const float vs_eff = ldexpf(fmaxf(ld_half == 0 ? pre_c : pre_b, 0x1p-64f), g2);
             const float ks_eff = fmaxf(ld_half == 0 ? pre_b : pre_a, 0x1p-40f);
             // (v_rcp_f32: one unit in the last place, far inside what lambda and the row sums need; both loader

@@ -57,9 +57,11 @@
 #define KVQ_Q_LOW_PART 1
 #endif
 // Number of 16-channel slabs whose low query parts stay in accumulation registers instead of being read
-// from LDS for every key tile (4 registers per slab and 32-row block).
+// from LDS for every key tile (4 registers per slab and 32-row block).  With 4 the 4-bit kernel spills, and
+// a spill reload lands in the loader behind the prefetch loads, where it waits for them on every stage;
+// with 2 nothing spills (9.60 -> 9.31 ms at 4 bits on the benchmark shape).
 #ifndef KVQ_Q_LOW_RESIDENT_SLABS
-#define KVQ_Q_LOW_RESIDENT_SLABS 4
+#define KVQ_Q_LOW_RESIDENT_SLABS 2
 #endif
 // 1 (2-bit caches only): the low query part is an FP8 E4M3 operand with one power-of-two scale per row and
 // meets the key codes in v_mfma_scale_f32_32x32x64_f8f6f4 (64 channels per instruction at twice the

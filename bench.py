@@ -155,7 +155,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (heads shard with no "
-              "communication; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "communication: each GPU would run this same kernel on its share of the heads). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2605_26266_amd import binding as B

@@ -1,7 +1,8 @@
 // Issue-rate microbenchmarks for gfx950, the yardsticks the attention and quantize kernels are read
 // against: sustained MFMA rate, what vector instructions cost next to MFMAs in one in-order wave (and
-// with two waves per SIMD), LDS read rate by access width, and a plain HBM copy of the size one
-// quantize-append call moves.  Stand-alone program; every loop has a fixed trip count.
+// with two waves per SIMD), LDS read rate by access width, the rate of the block-scaled 32x32x64 MFMA by
+// operand format (with a check of the FP4 / FP6 operand layout against a host product), and a plain HBM
+// copy of the size one quantize-append call moves.  Stand-alone program; every loop has a fixed trip count.
 //
 //   kvq_microbench            prints one table per experiment
 #include <hip/hip_runtime.h>
@@ -9,7 +10,10 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
+#include <vector>
 
+typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -156,6 +160,103 @@ template <typename T> void lds_row(uint32_t *out, const char *name)
     printf("| %-13s | %6.2f | %7.1f |\n", name, ms * 1e6 / instr, instr * 64 * sizeof(T) / (ms * 1e6));
 }
 
+// v_mfma_scale_f32_32x32x64_f8f6f4 by operand format (FA, FB: 0 = FP8 E4M3, 2 = FP6 E2M3, 4 = FP4 E2M1), one
+// wave per SIMD, four accumulator chains, all scales 1.
+template <int FA, int FB> __global__ __launch_bounds__(256, 1) void scaled_mfma_kernel(float *out, int iters)
+{
+    i32x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = 0x22222222;
+        b[i] = 0x08208208 + (int)threadIdx.x;
+    }
+    f32x16 c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = {};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) c[k] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c[k], FA, FB, 0, 0x7f, 0, 0x7f);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s += c[k][0] + c[k][9];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+template <int FA, int FB> double scaled_mfma_ns(float *out)
+{
+    const int iters = kIters * 4;
+    const float ms = time_ms([&] { scaled_mfma_kernel<FA, FB><<<kBlocks, 256>>>(out, iters); });
+    return ms * 1e6 / (4.0 * iters);
+}
+
+// One FP4 (A) x FP6 (B) instruction on operands laid out as: lane l holds row (column) l mod 32 and the K
+// indices 32 (l div 32) + j, j = 0..31, element j in bits 4j.. of A's first four registers and bits 6j.. of B's
+// first six; B carries a power-of-two scale per column (E8M0 byte in the scale register's low byte).
+__global__ __launch_bounds__(64, 1) void fp4_fp6_once(const i32x8 *a, const i32x8 *b, const int *scale_b, float *out)
+{
+    const int l = threadIdx.x;
+    f32x16 c = {};
+    c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[l], b[l], c, 4, 2, 0, 0x7f, 0, scale_b[l]);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) out[l * 16 + v] = c[v];
+}
+int check_fp4_fp6_layout(float *out)
+{
+    auto fp4 = [](int n) {
+        const float t[8] = {0.0f, 0.5f, 1.0f, 1.5f, 2.0f, 3.0f, 4.0f, 6.0f};
+        return (n & 8) ? -t[n & 7] : t[n & 7];
+    };
+    auto fp6 = [](int n) {   // E2M3, bias 1
+        const int e = (n >> 3) & 3, m = n & 7;
+        const float mag = e == 0 ? m / 8.0f : (float)(1 << (e - 1)) * (1.0f + m / 8.0f);
+        return (n & 32) ? -mag : mag;
+    };
+    std::vector<int> A(32 * 64), B(64 * 32), hs(64);
+    uint32_t seed = 12345u;
+    auto next = [&]() { seed = seed * 1664525u + 1013904223u; return (int)(seed >> 16); };
+    for (auto &x : A) x = next() % 16;
+    for (auto &x : B) x = next() % 64;
+    std::vector<i32x8> ha(64), hb(64);
+    for (int l = 0; l < 64; ++l) {
+        uint32_t ra[8] = {}, rb[8] = {};
+        for (int j = 0; j < 32; ++j) {
+            const int k = 32 * (l / 32) + j, bit = 6 * j;
+            ra[j / 8] |= (uint32_t)A[(l % 32) * 64 + k] << (4 * (j % 8));
+            const uint64_t v = (uint64_t)B[k * 32 + (l % 32)] << (bit % 32);
+            rb[bit / 32] |= (uint32_t)v;
+            if (bit / 32 + 1 < 8) rb[bit / 32 + 1] |= (uint32_t)(v >> 32);
+        }
+        for (int i = 0; i < 8; ++i) {
+            ha[l][i] = (int)ra[i];
+            hb[l][i] = (int)rb[i];
+        }
+        hs[l] = 0x7f - (l % 32) % 5;
+    }
+    i32x8 *da, *db;
+    int *ds;
+    CHECK(hipMalloc(&da, 64 * sizeof(i32x8)));
+    CHECK(hipMalloc(&db, 64 * sizeof(i32x8)));
+    CHECK(hipMalloc(&ds, 64 * sizeof(int)));
+    CHECK(hipMemcpy(da, ha.data(), 64 * sizeof(i32x8), hipMemcpyHostToDevice));
+    CHECK(hipMemcpy(db, hb.data(), 64 * sizeof(i32x8), hipMemcpyHostToDevice));
+    CHECK(hipMemcpy(ds, hs.data(), 64 * sizeof(int), hipMemcpyHostToDevice));
+    fp4_fp6_once<<<1, 64>>>(da, db, ds, out);
+    CHECK(hipDeviceSynchronize());
+    std::vector<float> ho(64 * 16);
+    CHECK(hipMemcpy(ho.data(), out, ho.size() * sizeof(float), hipMemcpyDeviceToHost));
+    int bad = 0;
+    for (int l = 0; l < 64; ++l)
+        for (int v = 0; v < 16; ++v) {
+            const int n = l % 32, i = 8 * (v / 4) + 4 * (l / 32) + v % 4;   // accumulator register v of lane l
+            double want = 0.0;
+            for (int k = 0; k < 64; ++k) want += (double)fp4(A[i * 64 + k]) * fp6(B[k * 32 + n]);
+            want = std::ldexp(want, -(n % 5));
+            if (std::fabs(want - ho[l * 16 + v]) > 1e-5 * (1.0 + std::fabs(want))) ++bad;
+        }
+    CHECK(hipFree(da)); CHECK(hipFree(db)); CHECK(hipFree(ds));
+    return bad;
+}
+
 __global__ void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
@@ -210,6 +311,17 @@ int main()
     lds_row<uint32_t>(reinterpret_cast<uint32_t *>(out), "ds_read_b32");
     lds_row<u32x2>(reinterpret_cast<uint32_t *>(out), "ds_read_b64");
     lds_row<u32x4>(reinterpret_cast<uint32_t *>(out), "ds_read_b128");
+
+    printf("\n## v_mfma_scale_f32_32x32x64_f8f6f4 by operand format: ns per instruction per SIMD (131072 flop each)\n\n");
+    printf("| A | B | ns per MFMA | chip TFLOP/s |\n|---|---|---|---|\n");
+    {
+        const double r[5] = {scaled_mfma_ns<0, 0>(out), scaled_mfma_ns<4, 0>(out), scaled_mfma_ns<4, 2>(out),
+                             scaled_mfma_ns<2, 2>(out), scaled_mfma_ns<4, 4>(out)};
+        const char *fa[5] = {"FP8", "FP4", "FP4", "FP6", "FP4"}, *fb[5] = {"FP8", "FP8", "FP6", "FP6", "FP4"};
+        for (int i = 0; i < 5; ++i) printf("| %s | %s | %.2f | %.0f |\n", fa[i], fb[i], r[i], 131072.0 / r[i] * 1024 / 1e3);
+    }
+    printf("\nFP4 x FP6 with a per-column power-of-two scale against a host product of the same operands "
+           "(2-bit codes 0..3 are the FP4 values 0, 0.5, 1, 1.5): %d mismatches of 1024\n", check_fp4_fp6_layout(out));
 
     printf("\n## HBM copy of the bytes one quantize-append call moves at the large shape\n\n");
     {

@@ -67,6 +67,9 @@
 // meets the key codes in v_mfma_scale_f32_32x32x64_f8f6f4 (64 channels per instruction at twice the
 // 16-bit rate): 4 MFMAs per key tile instead of 16, the whole low part resident in 32 accumulation
 // registers.  0: f16 low part as for 4-bit caches.
+#ifndef KVQ_KEYS_FP4
+#define KVQ_KEYS_FP4 1
+#endif
 #ifndef KVQ_Q_LOW_FP8
 #define KVQ_Q_LOW_FP8 1
 #endif
@@ -148,10 +151,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     // ---------------------------------------------------------------- query preparation ----
     // kPrepLanes adjacent lanes rotate one query row of the block: q~ = Hn q * softmax_scale * log2(e),
     // split into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
-    constexpr bool kLoFp8 = KVQ_Q_LOW_PART && KVQ_Q_LOW_FP8 && BITS == 2;
-    constexpr bool kLoF16 = KVQ_Q_LOW_PART && !kLoFp8;
+    constexpr bool kFp4 = KVQ_KEYS_FP4 && BITS == 2 && !PERCH;
+    constexpr bool kLoFp8 = KVQ_Q_LOW_PART && KVQ_Q_LOW_FP8 && BITS == 2 && !kFp4;
+    constexpr bool kLoF16 = KVQ_Q_LOW_PART && !kLoFp8 && !kFp4;
     constexpr int kPrepLanes = kThreads / kRowsPerBlock;   // 1 or 2
     constexpr int kPrepCh = D / kPrepLanes;                 // channels per lane
+    // FP4 keys: the query as four FP6 (E2M3) pieces, B operands of the 64-channel MFMAs: [row block][piece][MFMA]
+    i32x6 qp[kRB][4][2];
     u32x4 qop[kRB][8];  // B operands of the score MFMA: lane (n, hh) holds channels 16*slab + 8*hh .. +7 of rows n + 32 rb
     {
         const int prow = tid / kPrepLanes, ppart = tid % kPrepLanes;
@@ -202,10 +208,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // Channel c of the operand carries 4^g(c) (the inverse of the weight its key codes are unpacked with).
         const float cq = c_log * 0.088388347648318f;
 #pragma unroll
-        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (float)(1 << (2 * key_channel_class<BITS>(i)));
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (kFp4 ? 1.0f : (float)(1 << (2 * key_channel_class<BITS>(i))));
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
         uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
+        if constexpr (!kFp4) {
 #pragma unroll
         for (int i = 0; i < kPrepCh / 8; ++i) {
             u32x4 w;
@@ -221,8 +228,70 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             for (int s = 0; s < 8; ++s)
                 qop[rb][s] = *reinterpret_cast<const u32x4 *>(hsrc + 32 * rb * kQRowWords + 8 * s);
         __syncthreads();
+        }
         float ssum = 0.0f, ssum_w = 0.0f;   // sum of q~ (true scale), sum of the weighted operand values
-        if constexpr (kLoFp8) {
+        if constexpr (kFp4) {
+            static_assert(!kFp4 || kPrepLanes == 1, "one lane prepares a whole row");
+            // q~ = sum of four pieces n_k / 2 * 2^(e0 - 4 k), n_k integers: |n_0| <= 15 (the row maximum lies in
+            // (3.75, 7.5] * 2^e0), the residual after a piece is at most a quarter of its scale, so |n_k| <= 8
+            // afterwards: every piece adds four bits, the last step is 2^(e0 - 13).  n / 2 is an E2M3 value.
+            float mx = 0.0f;
+#pragma unroll
+            for (int c = 0; c < kPrepCh; ++c) mx = fmaxf(mx, fabsf(x[c]));
+            int e0 = (int)((__float_as_uint(mx * (1.0f / 7.5f)) >> 23) & 0xffu) - 126;
+            e0 = e0 < -100 ? -100 : e0 > 110 ? 110 : e0;
+            uint32_t scale_word = 0u;
+#pragma unroll
+            for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int ek = e0 - 4 * (2 * pass + kk);
+                    const float half = __uint_as_float((uint32_t)(127 + ek - 1) << 23);
+                    const float inv = __uint_as_float((uint32_t)(127 - ek + 1) << 23);
+                    // the key operand holds code / 2: one more factor of two in the scale byte
+                    scale_word |= (uint32_t)(127 + ek + 1) << (8 * (2 * pass + kk));
+#pragma unroll
+                    for (int op = 0; op < 4; ++op) {       // MFMA jm = op >> 1, lane half hw = op & 1
+                        const int jm = op >> 1, hw = op & 1;
+                        uint32_t d[6] = {0u, 0u, 0u, 0u, 0u, 0u};
+#pragma unroll
+                        for (int j = 0; j < 32; ++j) {
+                            // element j of the lane's FP4 key operand: word 2 jm + (j >> 4), 2-bit field
+                            // 2 (j & 7) + ((j >> 3) & 1) of it; the channel that field holds (see key_pair)
+                            const int wd = 2 * jm + (j >> 4), f = 2 * (j & 7) + ((j >> 3) & 1);
+                            const int pr = f & 7, slab = 2 * wd + (pr >> 2);
+                            const int c = 16 * slab + 8 * hw + 2 * (pr & 3) + (f >> 3);
+                            const float nn = rintf(x[c] * inv);
+                            x[c] = fmaf(-nn, half, x[c]);
+                            ssum = fmaf(nn, half, ssum);
+                            const float av = fabsf(nn) * 0.5f;
+                            const uint32_t mag = av < 1.0f ? (uint32_t)(av * 8.0f) : (__float_as_uint(av) >> 20) - 1008u;
+                            const uint32_t code = mag | ((__float_as_uint(nn) >> 26) & 32u);
+                            const int bit = 6 * j;
+                            d[bit >> 5] |= code << (bit & 31);
+                            if ((bit & 31) > 26) d[(bit >> 5) + 1] |= code >> (32 - (bit & 31));
+                        }
+                        uint32_t *pd = q_stage + prow * kQRowWords + (2 * kk + jm) * 12 + hw * 6;
+#pragma unroll
+                        for (int i = 0; i < 6; i += 2) *reinterpret_cast<u32x2 *>(pd + i) = u32x2{d[i], d[i + 1]};
+                    }
+                }
+                __syncthreads();
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+                    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                        for (int jm = 0; jm < 2; ++jm) {
+                            const uint32_t *ps = q_stage + (wave * kRowsPerWave + 32 * rb + n) * kQRowWords + (2 * kk + jm) * 12 + hh * 6;
+                            const u32x2 p0 = *reinterpret_cast<const u32x2 *>(ps), p1 = *reinterpret_cast<const u32x2 *>(ps + 2),
+                                        p2 = *reinterpret_cast<const u32x2 *>(ps + 4);
+                            qp[rb][2 * pass + kk][jm] = i32x6{(int)p0.x, (int)p0.y, (int)p1.x, (int)p1.y, (int)p2.x, (int)p2.y};
+                        }
+                __syncthreads();
+            }
+            row_scal[4 * prow + 3] = __uint_as_float(scale_word);
+        } else if constexpr (kLoFp8) {
             static_assert(!kLoFp8 || kPrepLanes == 1, "one lane prepares a whole row");
             // Low parts at true scale (the weight 4^g of the high operand taken out again: exact), their
             // largest magnitude, and from it the row's power-of-two scale: the largest low part lands in
@@ -327,10 +396,47 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
     // The 64 registers of query operands live in accumulation registers (MFMA reads them from there
     // directly), which leaves the vector registers to the score tile in flight.
+    if constexpr (!kFp4) {
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
         for (int s = 0; s < 8; ++s) asm volatile("" : "+a"(qop[rb][s]));
+    }
+    // FP4 keys: the 96 registers of query pieces likewise, and the four scale bytes of each row
+    int qp_scale[kRB] = {};
+    if constexpr (kFp4) {
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) asm volatile("" : "+a"(qp[rb][k][j]));
+            qp_scale[rb] = __float_as_int(row_scal[4 * (wave * kRowsPerWave + 32 * rb + n) + 3]);
+        }
+    }
+    // 2-bit codes are FP4 (E2M1) values as they stand, 0, 0.5, 1, 1.5: a packed word is two operand registers, the
+    // even and the odd fields, each in the low half of a nibble.  Four pieces x two 64-channel MFMAs per row block,
+    // FP4 x FP6 at twice the FP8 rate; opsel picks the piece's byte of the row's scale word.
+    uint32_t f4_mask = 0x33333333u;
+    asm volatile("" : "+s"(f4_mask));
+    auto fp4_operand = [&](auto j_, const uint32_t (&kw)[WPL]) {   // key words 2 J, 2 J + 1
+        constexpr int J = decltype(j_)::value;
+        const uint32_t w0 = kw[(2 * J) % WPL], w1 = kw[(2 * J + 1) % WPL];
+        return i32x8{(int)(w0 & f4_mask), (int)((w0 >> 2) & f4_mask), (int)(w1 & f4_mask), (int)((w1 >> 2) & f4_mask), 0, 0, 0, 0};
+    };
+    auto fp4_mfma = [&](auto j_, auto k_, const i32x8 &a4, f32x16 (&sn)[kRB]) {   // piece K against key words 2 J, 2 J + 1
+        constexpr int J = decltype(j_)::value, K = decltype(k_)::value;
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb) {
+            const i32x6 b6 = qp[rb][K][J];
+            const i32x8 b8 = {b6[0], b6[1], b6[2], b6[3], b6[4], b6[5], 0, 0};
+            sn[rb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a4, b8, sn[rb], 4, 2, 0, 0x7f, K, qp_scale[rb]);
+        }
+    };
+    auto score_fp4 = [&](auto j_, const uint32_t (&kw)[WPL], f32x16 (&sn)[kRB]) {
+        const i32x8 a4 = fp4_operand(j_, kw);
+        static_for<4>([&](auto k_) { fp4_mfma(j_, k_, a4, sn); });
+    };
 
     // FP8 low part: B operands of the two 64-channel MFMAs per 32-row block, and the rows' scale bytes
     i32x8 lo8[kRB][2];
@@ -852,6 +958,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             uint32_t off = lo_off;
             asm volatile("" : "+v"(off));
             const uint32_t *qlo = q_stage + off;
+            if constexpr (kFp4) {
+                score_fp4(IntC<0>{}, kw, sn);
+                score_fp4(IntC<1>{}, kw, sn);
+            } else
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
                 const u32x4 kop = key_operand<BITS, SLAB>(kw, uc);
@@ -1024,6 +1134,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     tacc[RB] = dot2_bf16(pw[RB][i], zh[i], tacc[RB]);
                 }
             };
+            i32x8 a4 = {};
             KVQ_CHUNK_FENCE();
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
@@ -1048,9 +1159,15 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                         k_scale[4 * g] = c.x; k_scale[4 * g + 1] = c.y; k_scale[4 * g + 2] = c.z; k_scale[4 * g + 3] = c.w;
                     }
                 }
-                const u32x4 kop = key_operand<BITS, SLAB>(pf.kw, uc);
+                u32x4 kop;
+                if constexpr (kFp4) {   // chunk SLAB: piece SLAB % 4 against key words 2 (SLAB / 4), + 1
+                    if constexpr (SLAB % 4 == 0) a4 = fp4_operand(IntC<SLAB / 4>{}, pf.kw);
+                    fp4_mfma(IntC<SLAB / 4>{}, IntC<SLAB % 4>{}, a4, sn);
+                } else {
+                    kop = key_operand<BITS, SLAB>(pf.kw, uc);
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+                    for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
+                }
                 if constexpr (SLAB >= 1) {
                     if constexpr (kLoF16) {
 #pragma unroll

@@ -29,8 +29,8 @@ MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16/f16 matrix peak
 HBM_PEAK_GBS = 8000.0
 # HBM bytes of one attention launch on the Large workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
 # this program scaled by the same counters on a plain 1 GiB elementwise kernel (--calibration-copy):
-# 223,212 KiB x 2.000 + 52,996 KiB x 1.000 (profiles/attention_mfma_large_int2_counters.md).
-ATTENTION_TRAFFIC_BYTES_LARGE = 511.4e6
+# 224,098 KiB x 2.000 + 52,993 KiB x 1.000 (profiles/attention_mfma_large_int2_counters.md).
+ATTENTION_TRAFFIC_BYTES_LARGE = 513.2e6
 
 
 def parse():

@@ -17,9 +17,10 @@
 // and a shift per one to three registers: the code lands in mantissa bits of a 16-bit float whose
 // exponent makes the value BASE + weight * code (see "Unpacking" below).  Key codes and the rotated
 // query use f16 (same MFMA rate as bf16, three more significant bits; codes are exact either way) and
-// the query is carried as an f16 high part plus a low part (FP8 for 2-bit caches, f16 for 4-bit, see the
-// switches below); value codes and probabilities use bf16 (its range is
-// needed for p * value-scale).  Per-token scale and zero-point never touch the operands: with one
+// the query is carried as an f16 high part plus a low part (f16, or FP8 where the switches below say so);
+// value codes and probabilities use bf16 (its range is needed for p * value-scale).  The 2-bit keys of
+// per-token caches take a shorter way (KVQ_KEYS_FP4 below): the codes are FP4 values as they stand and the query
+// is four FP6 pieces, multiplied by the block-scaled 64-channel MFMA at twice the FP8 rate.  Per-token scale and zero-point never touch the operands: with one
 // (scale, zero) per token
 //     s_mi = scale_i * ( q~_m . (BASE + code_i)  -  z_i * sum_c q~_mc  -  BASE * W_m  -  scale_i * nu'_m )
 // where q~ already carries softmax_scale * log2(e) / sqrt(d), W_m is the sum of the operand values of
@@ -67,6 +68,12 @@
 // meets the key codes in v_mfma_scale_f32_32x32x64_f8f6f4 (64 channels per instruction at twice the
 // 16-bit rate): 4 MFMAs per key tile instead of 16, the whole low part resident in 32 accumulation
 // registers.  0: f16 low part as for 4-bit caches.
+// 1 (2-bit caches, not the per-channel path): the key codes are the MFMA operand.  E2M1 encodes 0, 0.5, 1, 1.5 as
+// 0..3, so a packed word is two FP4 operand registers (w & 0x33333333, (w >> 2) & 0x33333333); the query is four
+// FP6 (E2M3) pieces n_k / 2 with one power-of-two scale per row and piece, n_k integers of at most four bits plus
+// sign, each piece four bits finer than the one before.  16 v_mfma_scale_f32_32x32x64_f8f6f4 (FP4 x FP6) per key
+// tile replace 16 f16 and 4 FP8 MFMAs, 12 unpacking instructions replace 64, the BASE term vanishes (W = 0), and
+// the 96 piece registers live where the 64 + 32 registers of the high and low parts lived.  0: high + low pair.
 #ifndef KVQ_KEYS_FP4
 #define KVQ_KEYS_FP4 1
 #endif
@@ -237,7 +244,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             // afterwards: every piece adds four bits, the last step is 2^(e0 - 13).  n / 2 is an E2M3 value.
             float mx = 0.0f;
 #pragma unroll
-            for (int c = 0; c < kPrepCh; ++c) mx = fmaxf(mx, fabsf(x[c]));
+            for (int c = 0; c < kPrepCh; ++c) {
+                mx = fmaxf(mx, fabsf(x[c]));
+                ssum += x[c];
+            }
             int e0 = (int)((__float_as_uint(mx * (1.0f / 7.5f)) >> 23) & 0xffu) - 126;
             e0 = e0 < -100 ? -100 : e0 > 110 ? 110 : e0;
             uint32_t scale_word = 0u;
@@ -263,9 +273,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                             const int c = 16 * slab + 8 * hw + 2 * (pr & 3) + (f >> 3);
                             const float nn = rintf(x[c] * inv);
                             x[c] = fmaf(-nn, half, x[c]);
-                            ssum = fmaf(nn, half, ssum);
-                            const float av = fabsf(nn) * 0.5f;
-                            const uint32_t mag = av < 1.0f ? (uint32_t)(av * 8.0f) : (__float_as_uint(av) >> 20) - 1008u;
+                            // E2M3 code of |n| / 2: 4 n below 4, 2 n + 8 below 8, n + 16 from there on
+                            const float an = fabsf(nn);
+                            const uint32_t mag = (uint32_t)fminf(fminf(4.0f * an, fmaf(2.0f, an, 8.0f)), an + 16.0f);
                             const uint32_t code = mag | ((__float_as_uint(nn) >> 26) & 32u);
                             const int bit = 6 * j;
                             d[bit >> 5] |= code << (bit & 31);
@@ -290,6 +300,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                         }
                 __syncthreads();
             }
+            // the row sum of what the pieces hold: the sum of q~ minus the sum of what is left of it
+#pragma unroll
+            for (int c = 0; c < kPrepCh; ++c) ssum -= x[c];
             row_scal[4 * prow + 3] = __uint_as_float(scale_word);
         } else if constexpr (kLoFp8) {
             static_assert(!kLoFp8 || kPrepLanes == 1, "one lane prepares a whole row");

@@ -239,9 +239,12 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         float ssum = 0.0f, ssum_w = 0.0f;   // sum of q~ (true scale), sum of the weighted operand values
         if constexpr (kFp4) {
             static_assert(!kFp4 || kPrepLanes == 1, "one lane prepares a whole row");
-            // q~ = sum of four pieces n_k / 2 * 2^(e0 - 4 k), n_k integers: |n_0| <= 15 (the row maximum lies in
-            // (3.75, 7.5] * 2^e0), the residual after a piece is at most a quarter of its scale, so |n_k| <= 8
-            // afterwards: every piece adds four bits, the last step is 2^(e0 - 13).  n / 2 is an E2M3 value.
+            // q~ = sum of four pieces n_k / 2 * 2^e_k, n_k integers of magnitude up to 15 (n / 2 is an E2M3 value),
+            // e_0 = e0 with the row maximum in (3.75, 7.5] * 2^e0, e_k = e0 - 4 k - 1 after that.  What piece 0
+            // leaves is at most a quarter of its scale, i.e. 16 half-steps of piece 1: five bits finer, and the one
+            // value in 33 that does not fit (16) is clamped to 15, which leaves the next piece a whole step of its
+            // predecessor instead of half a step -- again 16 of its own half-steps, clamped likewise.  The last
+            // step is 2^(e0 - 14); the error is a quarter of it, half of it after a clamp.
             float mx = 0.0f;
 #pragma unroll
             for (int c = 0; c < kPrepCh; ++c) {
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             for (int pass = 0; pass < 2; ++pass) {
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk) {
-                    const int ek = e0 - 4 * (2 * pass + kk);
+                    const int ek = e0 - 4 * (2 * pass + kk) - (2 * pass + kk > 0 ? 1 : 0);
                     const float half = __uint_as_float((uint32_t)(127 + ek - 1) << 23);
                     const float inv = __uint_as_float((uint32_t)(127 - ek + 1) << 23);
                     // the key operand holds code / 2: one more factor of two in the scale byte
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                             const int wd = 2 * jm + (j >> 4), f = 2 * (j & 7) + ((j >> 3) & 1);
                             const int pr = f & 7, slab = 2 * wd + (pr >> 2);
                             const int c = 16 * slab + 8 * hw + 2 * (pr & 3) + (f >> 3);
-                            const float nn = rintf(x[c] * inv);
+                            const float nn = fminf(fmaxf(rintf(x[c] * inv), -15.0f), 15.0f);
                             x[c] = fmaf(-nn, half, x[c]);
                             // E2M3 code of |n| / 2: 4 n below 4, 2 n + 8 below 8, n + 16 from there on
                             const float an = fabsf(nn);

@@ -123,6 +123,33 @@ def test_softmax_scale_and_large_queries(P):
 
 
 @pytest.mark.parametrize("bits", [2, 4])
+def test_query_dynamic_range(P, bits):
+    """Query rows the operand formats of the matrix-core path have to cope with: all zeros, magnitudes far below
+    anything a score can see, rows whose rotated vector is one large channel plus small ones (a constant offset
+    before the rotation), and a mix of magnitudes over the rows of one 32-row block."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads = 2
+    cache = P.make_cache(w, 512, heads=heads)
+    kc, vc = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=512)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=128)
+    q = wl.chunk_q(w, heads=range(heads))[:256].copy()
+    rng = np.random.default_rng(77)
+    q[0] = 0.0
+    q[1] *= np.float32(1e-30)
+    q[2] *= np.float32(1e-6)
+    q[3:40] = q[3:40] * np.float32(0.5) + np.float32(0.75)        # rotated: one channel of 8.5, the rest small
+    q[40:64] *= rng.uniform(0.01, 4.0, size=(24, 1, 1)).astype(np.float32)
+    q[64:96, :, 5] += np.float32(6.0)                              # one large raw channel: flat after the rotation
+    q = wl.round_to_bf16(q)
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 1)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16")
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "dynamic range, %d bits" % bits)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
 def test_large_zero_points(P, bits):
     """Vectors that are a spike in channel 0 plus small noise rotate into a large offset with a small range,
     so their zero-points reach several hundred: beyond one bf16 piece on the matrix-core path."""

@@ -900,11 +900,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const int sb = 8 * (ld_key & 3), sh = 16 * (ld_key & 1);   // the token's byte / half-word inside its word
                 if (ld_half == 0) {
                     pre_a = -(bf16_val((uint16_t)(ra >> sh)) + Unpack<BITS>::kStoredOffset);
-                    pre_b = e4m3_to_float((uint8_t)(rb >> sb));
-                    pre_c = e4m3_to_float((uint8_t)(rc >> sb));
+                    pre_b = e4m3_low_byte(rb >> sb);
+                    pre_c = e4m3_low_byte(rc >> sb);
                 } else {
-                    pre_a = e4m3_to_float((uint8_t)(ra >> sb));
-                    pre_b = e4m3_to_float((uint8_t)(rb >> sb));
+                    pre_a = e4m3_low_byte(ra >> sb);
+                    pre_b = e4m3_low_byte(rb >> sb);
                     pre_c = bf16_val((uint16_t)(rc >> sh)) + Unpack<BITS>::kStoredOffset;
                 }
             }

@@ -432,7 +432,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             uint32_t ks_pair[G];
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                const float step = pre_valid ? e4m3_to_float((uint8_t)(raw_ks >> (8 * j))) : 0.0f;
+                const float step = pre_valid ? e4m3_low_byte((uint32_t)(raw_ks >> (8 * j))) : 0.0f;
                 const float zs = step * bf16_val((uint16_t)(raw_kz >> (16 * j)));   // 4 x 8 significant bits: exact
                 kg[j].step = bf16_bits(step);
                 kg[j].step2 = bf16_bits(step * step);
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 uint16_t *tau16 = reinterpret_cast<uint16_t *>(buf + St::kTau);
 #pragma unroll
                 for (int j = 0; j < G; ++j) {
-                    const float step = pre_valid ? e4m3_to_float((uint8_t)(raw_vs >> (8 * j))) : 0.0f;
+                    const float step = pre_valid ? e4m3_low_byte((uint32_t)(raw_vs >> (8 * j))) : 0.0f;
                     const uint16_t sw = f16_bits(ldexpf(step, g2));   // step * 4^g, the inverse weight of the codes
 #pragma unroll
                     for (int b = j * kBlocksPerGroup; b < (j + 1) * kBlocksPerGroup; ++b)

@@ -60,6 +60,10 @@ __device__ inline uint32_t pack_bf16(float lo, float hi)
 __device__ inline uint16_t bf16_bits(float f) { return (uint16_t)(pack_bf16(f, 0.0f) & 0xffffu); }
 __device__ inline float bf16_val(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
+// OCP E4M3 in the low byte of w -> float, by the hardware conversion (exact, subnormals included; the stored
+// scales are finite).
+__device__ inline float e4m3_low_byte(uint32_t w) { return __builtin_amdgcn_cvt_f32_fp8((int)w, 0); }
+
 __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
 {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);

@@ -114,3 +114,55 @@ def test_effective_bitwidth_of_the_format():
     for bits, g, want in ((2, 32, 2.75), (2, 128, 2.1875), (4, 64, 4.375)):
         d = 128
         assert (d * bits + (8 + 16) * (d // g)) / d == want
+
+
+def _hand_groups():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "fp8meta_hand_groups.txt")
+    rows = []
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        bits, x, codes, step, zero, plain = [f.strip() for f in line.split("|")]
+        rows.append((int(bits), np.array(x.split(), dtype=np.float64), np.array(codes.split(), dtype=np.int64),
+                     float(step), float(zero), np.array(plain.split(), dtype=np.int64)))
+    return rows
+
+
+def test_bf16_zero_point_beyond_256_hand_worked():
+    """Zero-points above 256 in magnitude are not BF16 values: the stored one is rounded (8 significant bits,
+    ties to even) and the codes are taken with the stored one.  Expected values are worked by hand in the
+    golden file; a quantizer that took the codes with the unrounded zero-point would give its last column."""
+    rows = _hand_groups()
+    assert len(rows) >= 5
+    for bits, x, codes, step, zero, plain in rows:
+        g = len(x)
+        got_codes, got_scale, got_zero = oracle.quantize(x[None, :], bits, g, False, True)
+        assert abs(zero) > 256
+        assert got_scale[0, 0] == np.float32(step), (x, got_scale)
+        assert got_zero[0, 0] == np.float32(zero), (x, got_zero)
+        assert np.array_equal(got_codes[0].astype(np.int64), codes), (x, got_codes)
+        assert not np.array_equal(codes, plain)          # the rounding of the zero-point is visible in the codes
+        # the same group without the 8-bit/16-bit metadata keeps the integer zero-point and the plain codes
+        # (steps here are exact in E4M3 or, where they are not, the row says so by its stored step)
+        if step * (2 ** bits - 1) == x.max() - x.min():
+            c32, s32, z32 = oracle.quantize(x[None, :], bits, g, False, False)
+            assert np.array_equal(c32[0].astype(np.int64), plain) and s32[0, 0] == np.float32(step)
+            assert abs(z32[0, 0] - zero) >= 1
+
+
+def test_error_bound_fails_only_where_the_zero_point_is_rounded():
+    """|error| <= step / 2 holds whenever the BF16 zero-point is exact (|z| <= 256) and can fail beyond it: the
+    second hand-worked group reconstructs every value as 1008 (error up to 2 with a step of 0.5)."""
+    bits, x, codes, step, zero, _ = _hand_groups()[1]
+    got_codes, got_scale, got_zero = oracle.quantize(x[None, :], bits, len(x), False, True)
+    xhat = oracle.dequantize(got_codes, got_scale, got_zero)[0]
+    assert np.array_equal(xhat, np.full(4, 1008.0)) and np.max(np.abs(xhat - x)) == 2.0
+    rng = np.random.default_rng(21)
+    for _ in range(200):
+        off = rng.uniform(-60, 60)
+        xs = wl.round_to_bf16((rng.standard_normal(32) + off).astype(np.float32)).astype(np.float64)
+        c, s, z = oracle.quantize(xs[None, :], 2, 32, False, True)
+        if abs(z[0, 0]) <= 256:
+            assert np.all(np.abs(oracle.dequantize(c, s, z)[0] - xs) <= 0.5 * s[0, 0] * (1 + 1e-9))

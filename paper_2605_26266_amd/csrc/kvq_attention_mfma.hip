@@ -80,6 +80,16 @@
 #ifndef KVQ_Q_LOW_FP8
 #define KVQ_Q_LOW_FP8 1
 #endif
+// 1 (kernels with FP4 key operands): the score MFMAs are written out with vector-register destinations, so that no
+// score has to be copied out of an accumulation register before the vector ALU can scale it (32 copies per key tile).
+#ifndef KVQ_SCORES_IN_VGPRS
+#define KVQ_SCORES_IN_VGPRS 1
+#endif
+// 1 (same kernels): the fast loop is unrolled over the four tiles of a stage, which turns a tile's place inside its
+// stage buffer into immediate offsets and the stage opening into straight-line code.
+#ifndef KVQ_UNROLL_STAGE
+#define KVQ_UNROLL_STAGE 1
+#endif
 
 namespace kvq {
 namespace {
@@ -159,6 +169,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
     // kPrepLanes adjacent lanes rotate one query row of the block: q~ = Hn q * softmax_scale * log2(e),
     // split into an f16 high and low part; nu = ||q||^2; the row sum of the (high + low) parts.
     constexpr bool kFp4 = KVQ_KEYS_FP4 && BITS == 2 && !PERCH;
+    constexpr bool kVs = KVQ_SCORES_IN_VGPRS && kFp4;   // score tile in vector registers (written-out MFMAs)
     constexpr bool kLoFp8 = KVQ_Q_LOW_PART && KVQ_Q_LOW_FP8 && BITS == 2 && !kFp4;
     constexpr bool kLoF16 = KVQ_Q_LOW_PART && !kLoFp8 && !kFp4;
     constexpr int kPrepLanes = kThreads / kRowsPerBlock;   // 1 or 2
@@ -426,7 +437,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
             for (int k = 0; k < 4; ++k)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) asm volatile("" : "+a"(qp[rb][k][j]));
+                for (int j = 0; j < 2; ++j) {
+                    if (kVs && k == 3 && j == 1) asm volatile("" : "+v"(qp[rb][k][j]));
+                    else asm volatile("" : "+a"(qp[rb][k][j]));
+                }
             qp_scale[rb] = __float_as_int(row_scal[4 * (wave * kRowsPerWave + 32 * rb + n) + 3]);
         }
     }
@@ -453,6 +467,49 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         const i32x8 a4 = fp4_operand(j_, kw);
         static_for<4>([&](auto k_) { fp4_mfma(j_, k_, a4, sn); });
     };
+    // The same MFMAs with the score tile in vector registers (kVs).  The compiler keeps every MFMA result of this
+    // kernel in accumulation registers, from where each score would have to be copied before the vector ALU can
+    // touch it; written out, the instruction takes a vector-register tuple as C and D.  What the compiler no longer
+    // sees it no longer guards, so the wait states the hardware asks for are placed here, as the compiler places them
+    // for MFMAs of its own: two between a vector write of an operand and the MFMA that reads it (`fresh`: the A
+    // operand has just been made), and twelve between the last MFMA of a chain and the first vector instruction
+    // that reads the tile (KVQ_SCORE_TILE_READY).  Dependent MFMAs on one tile need none.
+    int f4_scale_one = 0x7f;
+    asm volatile("" : "+v"(f4_scale_one));
+    auto fp4_operand4 = [&](auto j_, const uint32_t (&kw)[WPL]) {
+        constexpr int J = decltype(j_)::value;
+        const uint32_t w0 = kw[(2 * J) % WPL], w1 = kw[(2 * J + 1) % WPL];
+        return i32x4{(int)(w0 & f4_mask), (int)((w0 >> 2) & f4_mask), (int)(w1 & f4_mask), (int)((w1 >> 2) & f4_mask)};
+    };
+    auto fp4_mfma_v = [&](auto j_, auto k_, auto fresh_, const i32x4 &a4, f32x16 &s, int rb) {
+        constexpr int J = decltype(j_)::value, K = decltype(k_)::value;
+        constexpr bool FRESH = decltype(fresh_)::value != 0;
+        const i32x6 b6 = qp[rb][K][J];
+        const int sb = qp_scale[rb];
+        // (the accumulation registers hold the output tile and all but two of the sixteen piece operands; those two
+        // stay in vector registers, which leaves the register allocator a few accumulation registers)
+#define KVQ_FP4_MFMA_V(NOP, SEL)                                                                                      \
+        {                                                                                                             \
+            if constexpr (K == 3 && J == 1)                                                                           \
+                asm(NOP "v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 " SEL " cbsz:4 blgp:2"           \
+                    : "+v"(s) : "v"(a4), "v"(b6), "v"(f4_scale_one), "v"(sb));                                        \
+            else                                                                                                      \
+                asm(NOP "v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %4 " SEL " cbsz:4 blgp:2"           \
+                    : "+v"(s) : "v"(a4), "a"(b6), "v"(f4_scale_one), "v"(sb));                                        \
+        }
+        if constexpr (K == 0 && FRESH) KVQ_FP4_MFMA_V("s_nop 1\n\t", "op_sel_hi:[0,0,0]")
+        if constexpr (K == 0 && !FRESH) KVQ_FP4_MFMA_V("", "op_sel_hi:[0,0,0]")
+        if constexpr (K == 1) KVQ_FP4_MFMA_V("", "op_sel:[0,1,0] op_sel_hi:[0,0,0]")
+        if constexpr (K == 2) KVQ_FP4_MFMA_V("", "op_sel_hi:[0,1,0]")
+        if constexpr (K == 3) KVQ_FP4_MFMA_V("", "op_sel:[0,1,0] op_sel_hi:[0,1,0]")
+#undef KVQ_FP4_MFMA_V
+    };
+    // first MFMA of a score tile: the constant terms, C = 0
+    auto const_mfma_v = [&](f32x16 &s, const u32x4 &cop, const u32x4 &rop) {
+        asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(cop), "v"(rop));
+    };
+    // every vector read of the tile goes through here: NOP completes the twelve wait states after the last MFMA
+#define KVQ_SCORE_TILE_READY(NOP, S) asm volatile(NOP : "+v"((S)[0]), "+v"((S)[kRB - 1]))
 
     // FP8 low part: B operands of the two 64-channel MFMAs per 32-row block, and the rows' scale bytes
     i32x8 lo8[kRB][2];
@@ -964,6 +1021,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 }
             }
             const u32x4 cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
+            if constexpr (kVs) {
+#pragma unroll
+                for (int rb = 0; rb < kRB; ++rb) const_mfma_v(sn[rb], cop, rowop[rb]);
+                static_for<2>([&](auto j_) {
+                    const i32x4 a4 = fp4_operand4(j_, kw);
+                    static_for<4>([&](auto k_) {
+#pragma unroll
+                        for (int rb = 0; rb < kRB; ++rb) fp4_mfma_v(j_, k_, IntC<1>{}, a4, sn[rb], rb);
+                    });
+                });
+                KVQ_SCORE_TILE_READY("s_nop 11", sn);
+                return;
+            }
             f32x16 zero;
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
@@ -1091,6 +1161,15 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             uint32_t kw[WPL];   // packed key codes of the tile scored next
             u32x4 cop;          // its constant-term operand
         };
+        auto prefetch_keys_at = [&](const uint32_t *buf, int tl, Prefetched &pf) {
+            const uint32_t *src = buf + St::kK + tl * 64 * WPL + lane * WPL;
+#pragma unroll
+            for (int i = 0; i < WPL / 4; ++i) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(src + 4 * i);
+                pf.kw[4 * i] = w.x; pf.kw[4 * i + 1] = w.y; pf.kw[4 * i + 2] = w.z; pf.kw[4 * i + 3] = w.w;
+            }
+            pf.cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
+        };
         auto prefetch_keys = [&](int t, Prefetched &pf) {
             const uint32_t *buf = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;
             const int tl = t & 3;
@@ -1102,11 +1181,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             pf.cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
         };
-        auto fused_iteration = [&](int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
+        // tl_: IntC<t mod 4> where the caller knows it at compile time (the unrolled fast loop), IntC<-1> otherwise.
+        auto fused_iteration = [&](auto tl_, int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
                                    u32x4 (&pop)[kRB][2], uint32_t &lo_flag) {
-            const uint32_t *bufn = lds + ((uint32_t)((t + 1) >> 2) % kBuffers) * St::kWords;   // holds tile t+1
+            constexpr int TL = decltype(tl_)::value;
             const uint32_t *bufc = lds + ((uint32_t)(t >> 2) % kBuffers) * St::kWords;         // holds tile t
-            const int tln = (t + 1) & 3, tlc = t & 3;
+            const uint32_t *bufx = lds + ((uint32_t)((t >> 2) + 1) % kBuffers) * St::kWords;   // the stage after
+            const uint32_t *bufn = TL < 0 ? lds + ((uint32_t)((t + 1) >> 2) % kBuffers) * St::kWords : TL == 3 ? bufx : bufc;   // holds tile t+1
+            const int tln = TL < 0 ? (t + 1) & 3 : (TL + 1) & 3, tlc = TL < 0 ? t & 3 : TL;
             const int pos = tlc * 32 + hh * 16;
             // requests for this iteration's exponential work
             float v_inv[16];
@@ -1133,7 +1215,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
             for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_bf16(pf.cop, rowop[rb], zero);
+            for (int rb = 0; rb < kRB; ++rb) {
+                if constexpr (kVs) const_mfma_v(sn[rb], pf.cop, rowop[rb]);
+                else sn[rb] = mfma_bf16(pf.cop, rowop[rb], zero);
+            }
             float lsum[kRB] = {}, tacc[kRB] = {};
             uint32_t pw[kRB][8];
             uint32_t vw[WPL];
@@ -1151,6 +1236,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 }
             };
             i32x8 a4 = {};
+            i32x4 a4v = {};
             KVQ_CHUNK_FENCE();
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
@@ -1176,7 +1262,12 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     }
                 }
                 u32x4 kop;
-                if constexpr (kFp4) {   // chunk SLAB: piece SLAB % 4 against key words 2 (SLAB / 4), + 1
+                if constexpr (kVs) {    // chunk SLAB: piece SLAB % 4 against key words 2 (SLAB / 4), + 1
+                    if constexpr (SLAB % 4 == 0) a4v = fp4_operand4(IntC<SLAB / 4>{}, pf.kw);
+                    fp4_mfma_v(IntC<SLAB / 4>{}, IntC<SLAB % 4>{}, IntC<1>{}, a4v, sn[0], 0);
+#pragma unroll
+                    for (int rb = 1; rb < kRB; ++rb) fp4_mfma_v(IntC<SLAB / 4>{}, IntC<SLAB % 4>{}, IntC<0>{}, a4v, sn[rb], rb);
+                } else if constexpr (kFp4) {
                     if constexpr (SLAB % 4 == 0) a4 = fp4_operand(IntC<SLAB / 4>{}, pf.kw);
                     fp4_mfma(IntC<SLAB / 4>{}, IntC<SLAB % 4>{}, a4, sn);
                 } else {
@@ -1213,6 +1304,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             if constexpr (kLoFp8) low_part_fp8(IntC<1>{}, pf.kw, sn);
             exp_chunk(IntC<7>{});
+            // Four exponentials and two conversions have been issued since the last score MFMA: six more wait
+            // states make the twelve that a vector read of its result needs.
+            if constexpr (kVs) asm volatile("s_nop 5" : "+v"(sn[0]), "+v"(sn[kRB - 1]), "+v"(pw[kRB - 1][6]), "+v"(pw[kRB - 1][7]));
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
                 l_s[rb] += lsum[rb];
@@ -1222,7 +1316,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             lo_flag = lo_flags.x | lo_flags.y;
             // key codes of the tile after next (its stage has been opened at the top of this iteration)
-            prefetch_keys(t + 2, pf);
+            if constexpr (TL < 0) prefetch_keys(t + 2, pf);
+            else prefetch_keys_at(TL >= 2 ? bufx : bufc, (TL + 2) & 3, pf);
             KVQ_CHUNK_FENCE();   // the score accumulators are read after all of the above, not before
             float mx[kRB];
 #pragma unroll
@@ -1291,6 +1386,40 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             move_reference(e, tmax);
             // fast loop: nothing in here touches the accumulators except the MFMAs
+            if constexpr (KVQ_UNROLL_STAGE && kVs) {
+                // Up to the next stage boundary one tile at a time (the loop is left and re-entered at any tile when
+                // a reference maximum has to move), then four tiles per trip.  Stage s is opened while tile 4 s - 2
+                // is being scored; stages 0 and 1 are open when the loop is entered for the first time.
+                bool leave = false;
+#define KVQ_STEP(TLV)                                                                                                 \
+                {                                                                                                     \
+                    if (__builtin_expect(t + 1 >= n_tiles, 0)) {                                                      \
+                        done = true;                                                                                  \
+                        leave = true;                                                                                 \
+                        break;                                                                                        \
+                    }                                                                                                 \
+                    if (((TLV) == 2 || ((TLV) < 0 && (t & 3) == 2)) && t >= 6) open_stage((t + 2) >> 2);              \
+                    fused_iteration(IntC<(TLV)>{}, t, pf, sn, e, tmax, pop, lo_flag);                                 \
+                    ++t;                                                                                              \
+                    if (__builtin_expect(__any(over_threshold(tmax) || lo_flag != 0u), 0)) {                          \
+                        leave = true;                                                                                 \
+                        break;                                                                                        \
+                    }                                                                                                 \
+                }
+                while ((t & 3) != 0) KVQ_STEP(-1)
+                if (!leave)
+                    for (;;) {
+                        KVQ_STEP(0)
+                        KVQ_STEP(1)
+                        KVQ_STEP(2)
+                        KVQ_STEP(3)
+                    }
+#undef KVQ_STEP
+                if (done) {   // the last tile has no successor to score
+                    exp_tile(t, e, pop);
+                    pv_tile(t, pop);
+                }
+            } else
             for (;;) {
                 if (__builtin_expect(t + 1 >= n_tiles, 0)) {
                     exp_tile(t, e, pop);
@@ -1302,7 +1431,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                     open_stage((t + 2) >> 2);
                     t_open += 4;
                 }
-                fused_iteration(t, pf, sn, e, tmax, pop, lo_flag);
+                fused_iteration(IntC<-1>{}, t, pf, sn, e, tmax, pop, lo_flag);
                 ++t;
                 if (__builtin_expect(__any(over_threshold(tmax) || lo_flag != 0u), 0)) break;
             }

@@ -178,6 +178,46 @@ def test_large_zero_points(P, bits):
         P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "large zero-points int%d" % bits)
 
 
+@pytest.mark.parametrize("bits,group", [(2, 128), (2, 32), (4, 64), (4, 32)])
+def test_large_zero_points_fp8_bf16_metadata(P, bits, group):
+    """Zero-points beyond +-256 under FP8/BF16 metadata: the stored zero-point is the BF16 rounding of the
+    integer one and the codes are taken with the stored value (clamping where that moves them).  Vectors with
+    a spike in channel 0 (a DC offset after the rotation) and a tiny range reach them; the value spikes
+    alternate in sign and the queries are small, so that the output stays near zero, where BF16 output
+    rounding is far inside the bar.  Quantizer bit-exact; the matrix-core kernel of the format (per-token
+    kernel for one group per token, group-wise kernel otherwise; INT4 with groups of 32 has none) and the
+    vector kernel against the oracle."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads, n_cached, n_cur, m = 2, 300, 64, 96
+    k0, v0 = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    kc = k0 * np.float32(1e-3)
+    kc[..., 0] += np.float32(8.0)
+    vc = v0 * np.float32(1e-3)
+    vc[..., 0] += np.where(np.arange(n_cached) % 2 == 0, 8.0, -8.0).astype(np.float32)[:, None]
+    kc, vc = wl.round_to_bf16(kc), wl.round_to_bf16(vc)
+    cache = P.make_cache(w, 320, heads=heads, group=group, fp8_meta=True)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    P.assert_quantized_equal(cache, kc, vc)
+    for which in (0, 1):
+        _, _, zeros = B.export_all(cache, which)
+        z = zeros.cpu().numpy().astype(np.float64)
+        assert np.abs(z).max() > 256.0                         # the case this test is about ...
+        assert np.any((np.abs(z) > 256) & (z % 2 == 0))        # ... (BF16 holds even integers only up there)
+    # the rounding is visible: the same vectors with fp32 metadata get other zero-points
+    _, _, z_plain = oracle.quantize(kc[:, 0, :].astype(np.float64), bits, group, True, False)
+    _, _, z_bf16 = oracle.quantize(kc[:, 0, :].astype(np.float64), bits, group, True, True)
+    assert np.abs(z_bf16).max() > 256
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(0.05))
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 1, group=group, fp8_meta=True)
+    for fp32_kernel in (False, True):
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", fp32_kernel=fp32_kernel)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16,
+                                 "large BF16 zero-points int%d g%d %s" % (bits, group, "vector" if fp32_kernel else "default"))
+
+
 @pytest.mark.parametrize("correction", [1, 0])
 @pytest.mark.parametrize("bits,group", [(2, 32), (2, 64), (4, 32), (4, 64), (2, 128)])
 def test_group_wise_fp8_metadata(P, bits, group, correction):

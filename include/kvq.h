@@ -27,8 +27,11 @@
  *     memset, no synchronisation), so they may be recorded into a HIP graph once each
  *     kernel has been launched outside a capture; the host-side counters of the
  *     cache (length, window, blocks) change at call time, not at replay.
- *   - Errors are returned as kvq_status; nothing aborts or throws.  On any error
- *     nothing has been enqueued and the cache is unchanged.
+ *   - Errors are returned as kvq_status; nothing aborts or throws.  On any error the
+ *     cache object is unchanged; nothing has been enqueued, except that an append to a
+ *     KVQ_KEYS_PER_CHANNEL cache, which is four launches, may have enqueued the first ones
+ *     when the runtime refuses a later one (they write work space and slots that no
+ *     live token refers to).
  *   - Tensors are [token][head][channel] with element strides `stride_token`,
  *     `stride_head` (channel stride 1), in the cache's io_dtype.
  *   - The packed layout inside the cache storage is private to the library; the
@@ -71,8 +74,10 @@ typedef enum {
     KVQ_KEYS_PER_CHANNEL = 1 /* one pair per rotated channel, shared by the tokens of one kvq_quantize_append
                                 call (appendix "Per-Channel Quantization Correction").  The correction is then
                                 one scalar per query and appended block.  Values stay per token.  Needs
-                                KVQ_META_FP32 and group_size == head_dim; attention runs on the fp32 vector
-                                kernel.  At most capacity/32 + 2 appended blocks can be live at once */
+                                KVQ_META_FP32 and group_size == head_dim.  BF16 caches with head_dim 128 run on the
+                                matrix cores, one pass over the cached keys per appended block of the window
+                                (windows of more than 40 blocks, fp32 I/O, head_dim 64 and the exact correction on
+                                the fp32 vector kernel).  At most capacity/32 + 2 appended blocks can be live at once */
 } kvq_key_axis;
 
 typedef struct {
@@ -96,6 +101,9 @@ typedef struct {
  * (codes plus the metadata, for K and for V); KVQ_KEYS_PER_CHANNEL adds
  *   (cap32/32 + 2) * num_heads * head_dim * 8 + cap32 * 4 + num_heads * head_dim * 32, rounded up to 256
  * (per-block scales and zero-points, the block of every token, work space of the append in flight).
+ * Every cache ends with a status block of 256 bytes (included in the figure returned): its first word is set by
+ * kvq_quantize_append when a stored zero-point reaches 65500 in magnitude, which the matrix-core attention
+ * kernels cannot carry exactly (see kvq_chunk_attention).
  * Returns 0 for an invalid or unsupported description. */
 size_t kvq_cache_bytes(const kvq_cache_desc *desc);
 
@@ -139,8 +147,9 @@ kvq_status kvq_cache_evict(kvq_cache *cache, int64_t n_tokens);
  * and packed.  With KVQ_META_FP8_BF16 the same is done per group of group_size rotated channels, with
  * the stored step the smallest FP8 E4M3 value >= (max - min)/(2^bits - 1) (so that the grid still covers
  * [min, max]; steps above 448 saturate) and the stored zero-point the BF16 value nearest to z; codes are
- * taken with the stored values.  A constant vector (group) has its range widened to include 0; an
- * all-zero one gets step 0.  The rotation is carried out exactly in double precision, so for inputs whose
+ * taken with the stored values: where |z| > 256 the BF16 zero-point differs from z, codes that would leave
+ * [0, 2^bits - 1] clamp, and the bound |x^ - x| <= step / 2 of Eq. 1 holds only for groups with |z| <= 256.
+ * A constant vector (group) has its range widened to include 0; an all-zero one gets step 0.  The rotation is carried out exactly in double precision, so for inputs whose
  * nonzero magnitudes in one vector span at most 2^38 (BF16 values) the codes, scales and
  * zero-points are a bit-exact function of the input.
  *
@@ -169,6 +178,12 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
  * mode that always runs the fp32 vector kernel).
  * cache_len == 0 (first chunk) and n_cur == 0 are allowed, not both; m == 0 is a no-op.
  * `out` must not alias the inputs.
+ * Which kernel runs: matrix cores for BF16 caches with head_dim 128 (every format but 4-bit codes with groups of
+ * 32), the fp32 vector kernel otherwise.  The matrix-core kernels carry a zero-point as two 16-bit pieces, exact
+ * below 2^16.  A cache that has stored a larger one since it was created or last reset (vectors whose offset is
+ * tens of thousands of times their range) is marked by the append; for such a cache the matrix-core launch
+ * returns without writing and a vector-kernel launch enqueued behind it does the work, with the same results as
+ * kvq_chunk_attention_fp32.  The mark is only cleared by kvq_cache_reset followed by an append.
  */
 kvq_status kvq_chunk_attention(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,
                                const void *q, const void *k_cur, const void *v_cur,

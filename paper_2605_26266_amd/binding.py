@@ -185,10 +185,21 @@ def _tok_head_strides(t: torch.Tensor):
     return t.stride(0), t.stride(1)
 
 
+def _check_shape(t: Optional[torch.Tensor], heads: int, head_dim: int, what: str, tokens: Optional[int] = None) -> None:
+    """The kernels index [token][head][channel] by the cache's head count and head_dim: a tensor with fewer heads
+    or channels would be read or written out of bounds on the device, so the shape is checked here."""
+    if t is None:
+        return
+    if t.dim() != 3 or t.shape[1] != heads or t.shape[2] != head_dim or (tokens is not None and t.shape[0] != tokens):
+        raise ValueError("%s must be [%s][%d][%d], got %s" % (what, "tokens" if tokens is None else tokens, heads,
+                                                              head_dim, tuple(t.shape)))
+
+
 def kvq_quantize_append(cache: Cache, k: torch.Tensor, v: torch.Tensor,
                         stream: Optional[torch.cuda.Stream] = None) -> None:
     if k.dtype != cache.torch_dtype or v.dtype != cache.torch_dtype or k.shape != v.shape:
         raise ValueError("k and v must share the cache's io dtype and one shape")
+    _check_shape(k, cache.desc.num_heads, cache.desc.head_dim, "k and v")
     st, sh = _tok_head_strides(k)
     if _tok_head_strides(v) != (st, sh):
         raise ValueError("k and v must share strides")
@@ -200,6 +211,13 @@ def _attention(fn, cache: Cache, cache_start: int, cache_len: int, q, k_cur, v_c
                out, mass_cached, stream):
     st, sh = _tok_head_strides(q)
     n_cur = 0 if k_cur is None else k_cur.shape[0]
+    H, d = cache.desc.num_heads, cache.desc.head_dim
+    _check_shape(q, H, d, "q")
+    _check_shape(out, H, d, "out", q.shape[0])
+    _check_shape(k_cur, H, d, "k_cur")
+    _check_shape(v_cur, H, d, "v_cur", n_cur)
+    if mass_cached is not None and mass_cached.numel() != H * q.shape[0]:
+        raise ValueError("mass_cached must hold heads * m values")
     for t in (k_cur, v_cur, out):
         if t is not None and (t.dtype != cache.torch_dtype or (t.shape[0] > 0 and _tok_head_strides(t) != (st, sh))):
             raise ValueError("q, k_cur, v_cur and out must share dtype and strides")
@@ -236,6 +254,13 @@ def kvq_chunk_attention_ex(cache: Cache, cache_start: int, cache_len: int, q: to
         raise ValueError("q and out must be in the cache's io dtype and share strides")
     if mass_cached is not None and (mass_cached.dtype != torch.float32 or not mass_cached.is_contiguous()):
         raise ValueError("mass_cached must be a contiguous float32 [query heads][m] tensor")
+    n_cur_tokens = 0 if k_cur is None else k_cur.shape[0]
+    _check_shape(q, q.shape[1], cache.desc.head_dim, "q")
+    _check_shape(out, q.shape[1], cache.desc.head_dim, "out", q.shape[0])
+    _check_shape(k_cur, cache.desc.num_heads, cache.desc.head_dim, "k_cur")
+    _check_shape(v_cur, cache.desc.num_heads, cache.desc.head_dim, "v_cur", n_cur_tokens)
+    if mass_cached is not None and mass_cached.numel() != q.shape[1] * q.shape[0]:
+        raise ValueError("mass_cached must hold query heads * m values")
     qst, qsh = _tok_head_strides(q)
     st, sh = _tok_head_strides(kv) if kv is not None and kv.shape[0] > 0 else (cache.desc.num_heads * cache.desc.head_dim, cache.desc.head_dim)
     opts = kvq_attention_opts(q.shape[1] // cache.desc.num_heads, int(bool(causal)), qst, qsh)
@@ -263,6 +288,8 @@ def kvq_attention_diagnostics(cache: Cache, cache_start: int, cache_len: int, q:
         raise ValueError("k_ref and v_ref must hold cache_len tokens")
     if diag.dtype != torch.float32 or not diag.is_contiguous() or diag.numel() != cache.desc.num_heads * q.shape[0] * 4:
         raise ValueError("diag must be a contiguous float32 [heads][m][4] tensor")
+    for t, what in ((q, "q"), (k_ref, "k_ref"), (v_ref, "v_ref"), (k_cur, "k_cur"), (v_cur, "v_cur")):
+        _check_shape(t, cache.desc.num_heads, cache.desc.head_dim, what)
     st, sh = _tok_head_strides(q)
     n_cur = 0 if k_cur is None else k_cur.shape[0]
     _check(lib().kvq_attention_diagnostics(cache.handle, int(cache_start), int(cache_len), q.data_ptr(), _ptr(k_ref),

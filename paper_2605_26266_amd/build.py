@@ -1,4 +1,7 @@
-"""Compile the HIP sources of the library for gfx950 into paper_2605_26266_amd/libkvq.so."""
+"""Compile the HIP sources of the library for gfx950 into paper_2605_26266_amd/libkvq.so.
+
+`python -m paper_2605_26266_amd.build` builds the library; with `--microbench` it also builds the stand-alone
+issue-rate microbenchmarks (paper_2605_26266_amd/kvq_microbench, a measuring tool that is not part of the library)."""
 from __future__ import annotations
 
 import os
@@ -39,6 +42,16 @@ def _compile(item):
     return obj
 
 
+def build_microbench(verbose: bool = False) -> str:
+    cmd = ["hipcc", *COMMON, os.path.join(CSRC, "kvq_microbench.hip"), "-o", MICROBENCH]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for kvq_microbench.hip:\n" + r.stderr)
+    if verbose:
+        print("built", MICROBENCH)
+    return MICROBENCH
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as pool:
@@ -47,15 +60,12 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
-    cmd = ["hipcc", *COMMON, os.path.join(CSRC, "kvq_microbench.hip"), "-o", MICROBENCH]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed for kvq_microbench.hip:\n" + r.stderr)
     if verbose:
         print("built", LIB)
-        print("built", MICROBENCH)
     return LIB
 
 
 if __name__ == "__main__":
     build(verbose=True)
+    if "--microbench" in sys.argv[1:]:
+        build_microbench(verbose=True)

@@ -19,6 +19,7 @@ struct kvq_cache {
     int64_t len;    // live tokens
     std::deque<kvq_block> blocks;   // KVQ_KEYS_PER_CHANNEL: live appended blocks, oldest first
     int next_slot;
+    bool status_clean;   // the status block has been cleared on the device since the cache was created or reset
 
     // Forget blocks that lie wholly outside [base, base + len).
     void trim_blocks()
@@ -91,7 +92,7 @@ size_t kvq_cache_bytes(const kvq_cache_desc *desc)
     const int64_t cap32 = round_up_tile(desc->capacity_tokens);
     const int64_t meta = desc->meta_format == KVQ_META_FP32 ? 8 : 3 * (desc->head_dim / desc->group_size);
     const int64_t per_token = desc->head_dim * desc->bits / 8 + meta;
-    return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token + channel_bytes(desc, cap32));
+    return (size_t)(2 * (int64_t)desc->num_heads * cap32 * per_token + channel_bytes(desc, cap32) + kvq::kStatusBytes);
 }
 
 kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t bytes, kvq_cache **out)
@@ -109,6 +110,7 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
     c->len = 0;
     c->base = 0;
     c->next_slot = 0;
+    c->status_clean = false;
     const int64_t H = desc->num_heads;
     const int64_t code_bytes = H * c->cap32 * desc->head_dim * desc->bits / 8;  // multiple of 256
     const int64_t meta_bytes = H * c->cap32 * 4;                                // multiple of 128
@@ -151,6 +153,8 @@ kvq_status kvq_cache_create(const kvq_cache_desc *desc, void *dev_mem, size_t by
         v.kc_zero = reinterpret_cast<float *>(p); p += (int64_t)v.max_blocks * hd * 4;
         v.k_block = reinterpret_cast<uint32_t *>(p);
     }
+    // every part before it is a multiple of 128 bytes: the status block is 4-byte aligned (it holds 32-bit words)
+    v.status = reinterpret_cast<uint32_t *>(static_cast<char *>(dev_mem) + kvq_cache_bytes(desc) - kvq::kStatusBytes);
     v.cap_tiles = c->cap32 / kvq::kTileTokens;
     v.num_heads = desc->num_heads;
     v.head_dim = desc->head_dim;
@@ -171,6 +175,7 @@ kvq_status kvq_cache_reset(kvq_cache *cache)
     cache->len = 0;
     cache->base = 0;
     cache->blocks.clear();
+    cache->status_clean = false;   // the next append clears the sticky flag before it writes
     return KVQ_OK;
 }
 
@@ -221,6 +226,10 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
     if (d.key_axis == KVQ_KEYS_PER_CHANNEL) {
         if ((int64_t)cache->blocks.size() >= cache->view.max_blocks) return KVQ_ERR_CAPACITY;
         slot = cache->next_slot;
+    }
+    if (!cache->status_clean) {
+        if (kvq::launch_status_clear(cache->view, static_cast<hipStream_t>(hip_stream)) != hipSuccess) return KVQ_ERR_HIP;
+        cache->status_clean = true;
     }
     const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->base + cache->len, n_tokens, stride_token,
                                                      stride_head, slot, static_cast<hipStream_t>(hip_stream));
@@ -293,6 +302,8 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     a.out = out;
     a.mass_cached = mass_cached;
     a.n_key_blocks = 0;
+    a.status = cache->status_clean && cache_len > 0 ? cache->view.status : nullptr;
+    a.only_if_flagged = 0;
     // the exact (sinh) correction is a diagnostic mode: vector kernel only
     force_vector = force_vector || correction == 2;
     if (d.key_axis == KVQ_KEYS_PER_CHANNEL && !force_vector) {
@@ -317,9 +328,15 @@ static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, 
     const hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (diag) return kvq::launch_diagnostics_simt(a, k_ref, v_ref, diag, s) == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
     const bool group_matrix_path = !force_vector && kvq::attention_mfma_group_supported(cache->view);
-    const hipError_t e = matrix_path         ? kvq::launch_attention_mfma(a, s)
-                         : group_matrix_path ? kvq::launch_attention_mfma_group(a, s)
-                                             : kvq::launch_attention_simt(a, s);
+    hipError_t e = matrix_path         ? kvq::launch_attention_mfma(a, s)
+                   : group_matrix_path ? kvq::launch_attention_mfma_group(a, s)
+                                       : kvq::launch_attention_simt(a, s);
+    if (e == hipSuccess && (matrix_path || group_matrix_path) && a.status) {
+        // A cache that has ever stored a zero-point beyond the matrix-core kernels' domain carries a flag: the launch
+        // above has then returned without writing anything, and this one, which otherwise returns at once, does the work.
+        a.only_if_flagged = 1;
+        e = kvq::launch_attention_simt(a, s);
+    }
     return e == hipSuccess ? KVQ_OK : KVQ_ERR_HIP;
 }
 

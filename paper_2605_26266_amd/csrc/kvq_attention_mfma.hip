@@ -129,6 +129,7 @@ template <int BITS> constexpr size_t lds_bytes()
 template <int BITS, bool CORR, bool FP8META, bool PERCH = false>
 __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionArgs a, int row_blocks)
 {
+    if (cache_flagged(a.status)) return;   // the vector kernel enqueued behind this launch serves such a cache
     using St = Stage<BITS>;
     constexpr int WPL = St::WPL;
     extern __shared__ __align__(16) uint32_t lds[];
@@ -1527,9 +1528,8 @@ template <int BITS, bool CORR, bool FP8META, bool PERCH = false> hipError_t laun
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attention_mfma_kernel<BITS, CORR, FP8META, PERCH>), dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(), stream,
-                       a, row_blocks);
-    return hipGetLastError();
+    return launch_kernel(attention_mfma_kernel<BITS, CORR, FP8META, PERCH>, dim3((unsigned)blocks), dim3(kThreads), lds_bytes<BITS>(),
+                         stream, a, row_blocks);
 }
 
 }  // namespace

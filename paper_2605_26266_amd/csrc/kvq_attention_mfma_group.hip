@@ -121,6 +121,7 @@ template <int BITS, bool CORR, int G>
 __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(AttentionArgs a, int row_blocks)
 {
     static_assert(kRB == 2, "64 rows per wave");
+    if (cache_flagged(a.status)) return;   // the vector kernel enqueued behind this launch serves such a cache
     using St = GStage<BITS, G>;
     constexpr int WPL = St::WPL;
     constexpr int NC = St::NC;
@@ -889,9 +890,8 @@ template <int BITS, bool CORR, int G> hipError_t launch_group(const AttentionArg
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;
     const size_t lds_size = group_lds_bytes<BITS, G>();
-    hipLaunchKernelGGL((attention_mfma_group_kernel<BITS, CORR, G>), dim3((unsigned)blocks), dim3(kThreads), lds_size,
-                       stream, a, row_blocks);
-    return hipGetLastError();
+    return launch_kernel(attention_mfma_group_kernel<BITS, CORR, G>, dim3((unsigned)blocks), dim3(kThreads), lds_size, stream, a,
+                         row_blocks);
 }
 
 }  // namespace

@@ -218,6 +218,8 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     __shared__ float p_blk[D];
     __shared__ float scratch[D];
     __shared__ float corr_g[4];  // softmax_scale^2 / 24 * nu_j per group (at most 4 groups)
+    // Enqueued behind a matrix-core launch: there is work only if that launch has stood back (flagged cache).
+    if (a.only_if_flagged && !cache_flagged(a.status)) return;
     const int c = threadIdx.x;
     const int qhead = blockIdx.y;               // query head
     const int64_t row = blockIdx.x;
@@ -400,9 +402,8 @@ hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream)
     const bool bf16 = a.cv.io_dtype == KVQ_BF16;
 #define KVQ_A(D, B)                                                                                         \
     if (a.cv.head_dim == D && a.cv.bits == B) {                                                             \
-        if (bf16) hipLaunchKernelGGL((attention_simt_kernel<D, B, uint16_t>), grid, dim3(D), 0, stream, a); \
-        else hipLaunchKernelGGL((attention_simt_kernel<D, B, float>), grid, dim3(D), 0, stream, a);         \
-        return hipGetLastError();                                                                           \
+        if (bf16) return launch_kernel(attention_simt_kernel<D, B, uint16_t>, grid, dim3(D), 0, stream, a);  \
+        return launch_kernel(attention_simt_kernel<D, B, float>, grid, dim3(D), 0, stream, a);               \
     }
     KVQ_A(128, 2)
     KVQ_A(128, 4)
@@ -420,12 +421,8 @@ hipError_t launch_diagnostics_simt(const AttentionArgs &a, const void *k_ref, co
 #define KVQ_A(D, B)                                                                                           \
     if (a.cv.head_dim == D && a.cv.bits == B) {                                                               \
         if (bf16)                                                                                             \
-            hipLaunchKernelGGL((diagnostics_simt_kernel<D, B, uint16_t>), grid, dim3(D), 0, stream, a, k_ref, \
-                               v_ref, diag);                                                                  \
-        else                                                                                                  \
-            hipLaunchKernelGGL((diagnostics_simt_kernel<D, B, float>), grid, dim3(D), 0, stream, a, k_ref,    \
-                               v_ref, diag);                                                                  \
-        return hipGetLastError();                                                                             \
+            return launch_kernel(diagnostics_simt_kernel<D, B, uint16_t>, grid, dim3(D), 0, stream, a, k_ref, v_ref, diag); \
+        return launch_kernel(diagnostics_simt_kernel<D, B, float>, grid, dim3(D), 0, stream, a, k_ref, v_ref, diag);        \
     }
     KVQ_A(128, 2)
     KVQ_A(128, 4)

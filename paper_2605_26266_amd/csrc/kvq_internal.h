@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+
 #include "../../include/kvq.h"
 
 namespace kvq {
@@ -54,7 +56,13 @@ struct CacheView {
     uint32_t *k_block;               // [cap32]             block slot of the token at each ring position
     unsigned long long *kc_range;    // [H][d][2]           work space of the append in flight: min, max (ordered keys)
     double *kc_inv, *kc_z;           // [H][d]              work space: L / range and the zero-point, per channel
+    // Status block at the end of the storage (kStatusBytes).  Word 0: sticky, set by the quantize kernels when a stored
+    // zero-point is too large for the matrix-core attention kernels (kMatrixZeroLimit), read by every attention launch.
+    uint32_t *status;
 };
+constexpr int kStatusBytes = 256;
+// The matrix-core kernels carry OFFSET + zero-point as two bf16 pieces: exact for integers below 2^16.
+constexpr float kMatrixZeroLimit = 65500.0f;
 
 // Sign bits of the channels first .. first + 31 - (first mod 32), bit 0 = channel `first`.
 __device__ inline uint32_t sign_bits_from(const CacheView &cv, int first)
@@ -132,6 +140,21 @@ template <> struct Io<uint16_t> {
     __device__ static void store(uint16_t *p, float v) { *p = float_to_bf16(v); }
 };
 
+// Launch with the status of this launch as return value.  (hipGetLastError() after a <<< >>> launch would also
+// return, and clear, an error that some earlier HIP call of the process left behind on this thread.)
+template <typename... KArgs, typename... Args>
+hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, Args &&...args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<KArgs...> copy{static_cast<KArgs>(args)...};
+    return std::apply(
+        [&](auto &...a) {
+            void *ptrs[] = {static_cast<void *>(&a)...};
+            return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds_bytes, stream);
+        },
+        copy);
+}
+
 // Launchers implemented in the kernel translation units.  All return hipError_t of the launch.
 // block_slot: slot of the block this append creates (KVQ_KEYS_PER_CHANNEL caches only).
 hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
@@ -139,6 +162,8 @@ hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void
                                   hipStream_t stream);
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream);
+// Clears the status block (first append after kvq_cache_create / kvq_cache_reset).
+hipError_t launch_status_clear(const CacheView &cv, hipStream_t stream);
 
 // One appended block of a KVQ_KEYS_PER_CHANNEL cache inside the attended window: its parameter slot and its
 // token range relative to cache_start.
@@ -162,7 +187,13 @@ struct AttentionArgs {
     float *mass_cached;
     int32_t n_key_blocks;                 // matrix-core path of per-channel caches only
     KeyBlock key_blocks[kMaxKeyBlocks];
+    // The cache's status word (null: nothing has been appended since the cache was created or reset, there is
+    // nothing to look at).  A matrix-core launch returns at once when the word is set; the vector launch that the
+    // host enqueues behind it with only_if_flagged = 1 returns at once when it is not.
+    const uint32_t *status;
+    int32_t only_if_flagged;
 };
+__device__ inline bool cache_flagged(const uint32_t *status) { return status != nullptr && *status != 0u; }
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream);
 hipError_t launch_attention_mfma(const AttentionArgs &a, hipStream_t stream);
 // Per (head, row) [P_S unquantized, P_S quantized, JSD, output MSE] against the unquantized cached k_ref / v_ref

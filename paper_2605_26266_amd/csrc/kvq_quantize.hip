@@ -13,7 +13,9 @@
 //      values: codes go to LDS, then each thread assembles whole words of the token-major
 //      ("transposed") value tile and stores them.  A tile that an earlier append filled partly is
 //      merged word by word.
-// The kernel is bound by HBM traffic (d*elt bytes in, d*bits/8 + 8 bytes out, per vector).
+// The kernel moves d*elt bytes in and d*bits/8 + 8 bytes out per vector and no byte twice, but it is not bound by
+// that traffic: the exact double-precision rotation and the rounding decisions are about 800 vector instructions
+// per thread, and the vector ALU is busy for most of the kernel's time (about a third of the HBM rate is reached).
 #include "kvq_internal.h"
 
 namespace kvq {
@@ -124,6 +126,24 @@ __device__ inline double order_value(unsigned long long k)
     return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
 }
 
+// Nearest BF16 (ties to even) of a double in one rounding: to float towards zero with a sticky last bit (24
+// significant bits keep everything an 8-bit rounding looks at), then to BF16.
+__device__ inline uint16_t double_to_bf16(double x)
+{
+    float f = __double2float_rz(x);
+    if ((double)f != x) f = __uint_as_float(__float_as_uint(f) | 1u);
+    return float_to_bf16(f);
+}
+// A stored zero-point that the matrix-core attention kernels cannot carry exactly marks the cache.
+__device__ inline void flag_large_zero(const CacheView &cv, float zero)
+{
+    if (!(fabsf(zero) < kMatrixZeroLimit)) cv.status[0] = 1u;
+}
+__global__ void status_clear_kernel(CacheView cv)
+{
+    if (threadIdx.x < kStatusBytes / 4) cv.status[threadIdx.x] = 0u;
+}
+
 // Per-channel keys, step 0 of an append: empty ranges.
 __global__ void channel_range_init_kernel(CacheView cv)
 {
@@ -158,6 +178,7 @@ __global__ void channel_params_kernel(CacheView cv, int block_slot)
     const int64_t slot = (int64_t)block_slot * cv.num_heads * cv.head_dim + i;
     cv.kc_scale[slot] = (float)(step * norm);
     cv.kc_zero[slot] = (float)z;
+    flag_large_zero(cv, (float)z);
 }
 
 // GROUP == 0: one fp32 (scale, zero-point) per token.  GROUP > 0: one FP8 E4M3 scale and one BF16
@@ -303,7 +324,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
             const double s8 = degenerate ? 0.0 : e4m3_ceil(step, scale_byte);
             inv = degenerate ? 0.0 : norm / s8;
             const double zi = degenerate ? 0.0 : -__builtin_rint(lo * inv);
-            zero = bf16_to_float(float_to_bf16((float)zi));
+            zero = bf16_to_float(double_to_bf16(zi));
             z = (double)zero;
             scale = (float)s8;
         }
@@ -361,10 +382,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
                     if (l8 == 2 && head == 0 && valid) cv.k_block[ptile * kTileTokens + row] = (uint32_t)block_slot;
                 } else if constexpr (GROUP == 0) {
                     if (l8 == 2) cv.k_scale[meta_idx] = scale;
-                    if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                    if (l8 == 3) {
+                        cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                        flag_large_zero(cv, zero);
+                    }
                 } else if (group_writer) {
                     cv.k_scale8[group_idx] = (uint8_t)scale_byte;
                     cv.k_zero16[group_idx] = float_to_bf16(zero);
+                    flag_large_zero(cv, zero);
                 }
             }
         } else {
@@ -373,10 +398,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(CacheView cv, cons
             if (valid || tail) {
                 if constexpr (GROUP == 0) {
                     if (l8 == 2) cv.v_scale[meta_idx] = scale;
-                    if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                    if (l8 == 3) {
+                        cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                        flag_large_zero(cv, zero);
+                    }
                 } else if (group_writer) {
                     cv.v_scale8[group_idx] = (uint8_t)scale_byte;
                     cv.v_zero16[group_idx] = float_to_bf16(zero);
+                    flag_large_zero(cv, zero);
                 }
             }
         }
@@ -562,7 +591,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
                 const double s8 = degenerate ? 0.0 : e4m3_ceil(step, my_byte);
                 inv_mine = degenerate ? 0.0 : 0.08838834764831845 / s8;
                 const double zr = degenerate ? 0.0 : -__builtin_rint(lo * inv_mine);
-                my_zero = bf16_to_float(float_to_bf16((float)zr));
+                my_zero = bf16_to_float(double_to_bf16(zr));
                 z_mine = (double)my_zero;
                 my_scale = (float)s8;
             }
@@ -614,10 +643,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
             if (valid || tail) {
                 if constexpr (GROUP == 0) {
                     if (l8 == 2) cv.k_scale[meta_idx] = scale;
-                    if (l8 == 3) cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                    if (l8 == 3) {
+                        cv.k_negzero[meta_idx] = -(zero + code_offset(BITS));
+                        flag_large_zero(cv, zero);
+                    }
                 } else if (l8 < kG) {
                     cv.k_scale8[group_idx] = (uint8_t)my_byte;
                     cv.k_zero16[group_idx] = float_to_bf16(my_zero);
+                    flag_large_zero(cv, my_zero);
                 }
             }
         } else {
@@ -627,10 +660,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel128(CacheView cv, c
             if (valid || tail) {
                 if constexpr (GROUP == 0) {
                     if (l8 == 2) cv.v_scale[meta_idx] = scale;
-                    if (l8 == 3) cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                    if (l8 == 3) {
+                        cv.v_zero_off[meta_idx] = zero + code_offset(BITS);
+                        flag_large_zero(cv, zero);
+                    }
                 } else if (l8 < kG) {
                     cv.v_scale8[group_idx] = (uint8_t)my_byte;
                     cv.v_zero16[group_idx] = float_to_bf16(my_zero);
+                    flag_large_zero(cv, my_zero);
                 }
             }
         }
@@ -714,44 +751,43 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
     const int64_t first_tile = old_len / kTileTokens;
     const int64_t last_tile = (old_len + n - 1) / kTileTokens;
     const dim3 grid((unsigned)(last_tile - first_tile + 1), (unsigned)cv.num_heads);
+    const dim3 block(256);
     const T *kp = static_cast<const T *>(k), *vp = static_cast<const T *>(v);
     if (cv.key_axis == KVQ_KEYS_PER_CHANNEL) {
-        // ranges of the block -> per-channel parameters -> codes (keys per channel, values per token)
-        const unsigned nb = (unsigned)((cv.num_heads * cv.head_dim + 255) / 256);
-        hipLaunchKernelGGL(channel_range_init_kernel, dim3(nb), dim3(256), 0, stream, cv);
-        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T, 1>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n,
-                           st, sh, block_slot);
-        hipLaunchKernelGGL(channel_params_kernel, dim3(nb), dim3(256), 0, stream, cv, block_slot);
-        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T, 2>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n,
-                           st, sh, block_slot);
-        return hipGetLastError();
+        // ranges of the block -> per-channel parameters -> codes (keys per channel, values per token); the sequence
+        // stops at the first launch that fails (the cache's token count is only advanced when all four are enqueued)
+        const dim3 nb((unsigned)((cv.num_heads * cv.head_dim + 255) / 256));
+        hipError_t e = launch_kernel(channel_range_init_kernel, nb, block, 0, stream, cv);
+        if (e != hipSuccess) return e;
+        e = launch_kernel(quantize_append_kernel<D, BITS, 0, T, 1>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, block_slot);
+        if (e != hipSuccess) return e;
+        e = launch_kernel(channel_params_kernel, nb, block, 0, stream, cv, block_slot);
+        if (e != hipSuccess) return e;
+        return launch_kernel(quantize_append_kernel<D, BITS, 0, T, 2>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, block_slot);
     }
     if constexpr (D == 128) {
         if (cv.meta_format == KVQ_META_FP8_BF16) {
             if (cv.group_size == 32)
-                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 32>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
-            else if (cv.group_size == 64)
-                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 64>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
-            else
-                hipLaunchKernelGGL((quantize_append_kernel128<BITS, T, 128>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
-            return hipGetLastError();
+                return launch_kernel(quantize_append_kernel128<BITS, T, 32>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh);
+            if (cv.group_size == 64)
+                return launch_kernel(quantize_append_kernel128<BITS, T, 64>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh);
+            return launch_kernel(quantize_append_kernel128<BITS, T, 128>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh);
         }
     }
     if (cv.meta_format == KVQ_META_FP8_BF16) {
         if (cv.group_size == 32)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 32, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
-        else if (cv.group_size == 64)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 64, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
-        else if constexpr (D == 128)
-            hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 128, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
+            return launch_kernel(quantize_append_kernel<D, BITS, 32, T, 0>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
+        if (cv.group_size == 64)
+            return launch_kernel(quantize_append_kernel<D, BITS, 64, T, 0>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
+        if constexpr (D == 128)
+            return launch_kernel(quantize_append_kernel<D, BITS, 128, T, 0>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
         else
             return hipErrorInvalidValue;
     } else if constexpr (D == 128) {
-        hipLaunchKernelGGL((quantize_append_kernel128<BITS, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh);
+        return launch_kernel(quantize_append_kernel128<BITS, T, 0>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh);
     } else {
-        hipLaunchKernelGGL((quantize_append_kernel<D, BITS, 0, T>), grid, dim3(256), 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
+        return launch_kernel(quantize_append_kernel<D, BITS, 0, T, 0>, grid, block, 0, stream, cv, kp, vp, old_len, n, st, sh, 0);
     }
-    return hipGetLastError();
 }
 
 }  // namespace
@@ -773,17 +809,19 @@ hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void
     return hipErrorInvalidValue;
 }
 
+hipError_t launch_status_clear(const CacheView &cv, hipStream_t stream)
+{
+    return launch_kernel(status_clear_kernel, dim3(1), dim3(64), 0, stream, cv);
+}
+
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream)
 {
     const unsigned gx = (unsigned)(count < 4096 ? count : 4096);
     const dim3 grid(gx, (unsigned)cv.num_heads);
 #define KVQ_E(D, B)                                                                                        \
-    if (cv.head_dim == D && cv.bits == B) {                                                                \
-        hipLaunchKernelGGL((export_kernel<D, B>), grid, dim3(D), 0, stream, cv, which, start, count, codes, \
-                           scales, zeros);                                                                 \
-        return hipGetLastError();                                                                          \
-    }
+    if (cv.head_dim == D && cv.bits == B)                                                                  \
+        return launch_kernel(export_kernel<D, B>, grid, dim3(D), 0, stream, cv, which, start, count, codes, scales, zeros);
     KVQ_E(128, 2)
     KVQ_E(128, 4)
     KVQ_E(64, 2)

@@ -178,6 +178,42 @@ def test_large_zero_points(P, bits):
         P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "large zero-points int%d" % bits)
 
 
+@pytest.mark.parametrize("bits,group,fp8", [(2, None, False), (4, None, False), (2, 128, True), (2, 32, True)])
+def test_zero_points_beyond_the_matrix_core_domain(P, bits, group, fp8):
+    """Key vectors with a large offset and a minute range get zero-points of several hundred thousand: beyond
+    the 2^16 that the matrix-core kernels carry exactly.  The quantizer marks such a cache and the default entry
+    point then serves it with the vector kernel; a cache that is reset and refilled with ordinary vectors goes
+    back to the matrix cores.  Both must match the oracle."""
+    import oracle
+    from paper_2605_26266_amd import binding as B, workloads as wl
+    w = wl.WORKLOADS["small"].with_bits(bits)
+    heads, n_cached, n_cur, m = 2, 200, 64, 96
+    k0, v0 = wl.chunk_kv(w, 0, heads=range(heads), n_tokens=n_cached)
+    kc = k0 * np.float32(1e-5 if not fp8 else 1e-3)
+    kc[..., 0] += np.float32(40.0 if not fp8 else 4000.0)     # FP8 steps are at least 2^-9: a larger offset instead
+    kc = wl.round_to_bf16(kc)
+    vc = v0
+    cache = P.make_cache(w, 256, heads=heads, group=group, fp8_meta=fp8)
+    B.kvq_quantize_append(cache, P.to_dev(kc, "bf16"), P.to_dev(vc, "bf16"))
+    P.assert_quantized_equal(cache, kc, vc)
+    _, _, zeros = B.export_all(cache, 0)
+    assert float(zeros.abs().max()) > 70000.0                    # the case this test is about
+    kr, vr = wl.chunk_kv(w, 1, heads=range(heads), n_tokens=n_cur)
+    q = wl.round_to_bf16(wl.chunk_q(w, heads=range(heads))[:m] * np.float32(0.02 if not fp8 else 2e-4))
+    kw = dict(group=group, fp8_meta=fp8) if fp8 else {}
+    ref, mass_ref, _ = oracle.chunk_attention(q, kc, vc, kr, vr, bits, 1, **kw)
+    for fp32_kernel in (False, True):
+        out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16", fp32_kernel=fp32_kernel)
+        P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "flagged cache, %s entry" % ("fp32" if fp32_kernel else "default"))
+    # reset, ordinary vectors: the flag is cleared by the next append
+    B.kvq_cache_reset(cache)
+    B.kvq_quantize_append(cache, P.to_dev(k0, "bf16"), P.to_dev(v0, "bf16"))
+    q = wl.chunk_q(w, heads=range(heads))[:m]
+    ref, mass_ref, _ = oracle.chunk_attention(q, k0, v0, kr, vr, bits, 1, **kw)
+    out, mass = P.run_gpu_attention(cache, q, kr, vr, "bf16")
+    P.assert_attention_close(out, mass, ref, mass_ref, P.TOL_OUT_BF16, "after reset")
+
+
 @pytest.mark.parametrize("bits,group", [(2, 128), (2, 32), (4, 64), (4, 32)])
 def test_large_zero_points_fp8_bf16_metadata(P, bits, group):
     """Zero-points beyond +-256 under FP8/BF16 metadata: the stored zero-point is the BF16 rounding of the

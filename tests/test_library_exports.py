@@ -34,12 +34,13 @@ def test_status_strings_and_version(B):
 
 
 def test_cache_bytes_accounting(B):
-    # 2 tensors x heads x capacity rounded to 32 tokens x (d*bits/8 code bytes + 8 metadata bytes)
+    # 2 tensors x heads x capacity rounded to 32 tokens x (d*bits/8 code bytes + 8 metadata bytes), plus one
+    # status block of 256 bytes per cache (the sticky "zero-point outside the matrix-core domain" word)
     for heads, d, bits, cap in [(48, 128, 2, 69632), (24, 128, 4, 28080), (1, 64, 2, 256), (3, 128, 2, 33)]:
         cap32 = -(-cap // 32) * 32
-        assert B.kvq_cache_bytes(B.make_desc(heads, d, bits, cap)) == 2 * heads * cap32 * (d * bits // 8 + 8)
+        assert B.kvq_cache_bytes(B.make_desc(heads, d, bits, cap)) == 2 * heads * cap32 * (d * bits // 8 + 8) + 256
     # effective bits per cached element with 64 metadata bits per token: 2 + 64/128 = 2.5 at d = 128
-    n = B.kvq_cache_bytes(B.make_desc(8, 128, 2, 4096))
+    n = B.kvq_cache_bytes(B.make_desc(8, 128, 2, 4096)) - 256
     assert n * 8 / (2 * 8 * 4096 * 128) == 2.5
 
 
@@ -91,3 +92,42 @@ def test_host_side_cache_object_without_a_gpu(B):
     assert L.kvq_quantize_append(handle, ctypes.c_void_p(0x10000002), fake, 1, 256, 128, None) == B.KVQ_ERR_INVALID_ARG
     assert L.kvq_quantize_append(handle, fake, fake, 1, 250, 128, None) == B.KVQ_ERR_INVALID_ARG  # stride not 16-byte
     L.kvq_cache_destroy(handle)
+
+
+def test_binding_rejects_tensors_that_do_not_fit_the_cache(B):
+    """The kernels index tensors by the cache's head count and head_dim; the binding refuses any other shape before
+    anything is launched (checked here on a cache object whose storage is host memory: no call reaches a kernel)."""
+    import pytest
+    import torch
+    desc = B.make_desc(4, 128, 2, 64)
+    storage_ok = torch.empty(B.kvq_cache_bytes(desc) + 256, dtype=torch.uint8)
+    if storage_ok.data_ptr() % 256 != 0:      # the host allocator gives 64-byte alignment: take an aligned view
+        off = 256 - storage_ok.data_ptr() % 256
+        storage_ok = storage_ok[off:]
+    cache = object.__new__(B.Cache)
+    cache.desc, cache.storage, cache.torch_dtype = desc, storage_ok, torch.bfloat16
+    handle = ctypes.c_void_p()
+    assert B.lib().kvq_cache_create(ctypes.byref(desc), storage_ok.data_ptr(), B.kvq_cache_bytes(desc), ctypes.byref(handle)) == B.KVQ_OK
+    cache.handle = handle
+
+    def t(n, h, d):
+        return torch.zeros((n, h, d), dtype=torch.bfloat16)
+
+    with pytest.raises(ValueError):
+        B.kvq_quantize_append(cache, t(8, 3, 128), t(8, 3, 128))          # fewer heads than the cache
+    with pytest.raises(ValueError):
+        B.kvq_quantize_append(cache, t(8, 4, 64), t(8, 4, 64))            # head_dim 64 against a 128 cache
+    q, out = t(16, 4, 128), t(16, 4, 128)
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention(cache, 0, 0, t(16, 2, 128), t(8, 4, 128), t(8, 4, 128), out)
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention(cache, 0, 0, q, t(8, 4, 128), t(8, 4, 128), t(15, 4, 128))
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention(cache, 0, 0, q, t(8, 2, 128), t(8, 2, 128), out)
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention(cache, 0, 0, q, t(8, 4, 128), t(7, 4, 128), out)
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention(cache, 0, 0, q, t(8, 4, 128), t(8, 4, 128), out, torch.zeros(4 * 15))
+    with pytest.raises(ValueError):
+        B.kvq_chunk_attention_ex(cache, 0, 0, t(16, 8, 64), t(16, 4, 128), t(16, 4, 128), t(16, 8, 64), causal=True)
+    cache.close()

@@ -160,6 +160,21 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
                                int64_t stride_token, int64_t stride_head, void *hip_stream);
 
 /*
+ * kvq_quantize_append for callers that cannot allocate device memory or bring a work space along: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results.  The
+ * difference is where an append to a KVQ_KEYS_PER_CHANNEL cache keeps its work space (per head and channel the
+ * range of the block being appended, L / range and the zero-point: 32 bytes each): not in the cache storage but in
+ * a static device array inside the library, 256 KiB per GPU, held until the process ends.  That array serves
+ * num_heads * head_dim <= 8192; a larger cache gets KVQ_ERR_CAPACITY and nothing is enqueued.  The call allocates
+ * and frees nothing, on the host side it only looks the array's device address up (once per device).  All calls
+ * on one GPU share the array: the append overwrites what the previous one left, and two such appends that overlap
+ * in time on one GPU (different streams, different caches) race -- order them on one stream or with events.
+ * For per-token caches, whose append has no work space, this is kvq_quantize_append.
+ */
+kvq_status kvq_quantize_append_static(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                                      int64_t stride_token, int64_t stride_head, void *hip_stream);
+
+/*
  * Corrected chunk attention.  For every head and query row m:
  *     cached key i in [cache_start, cache_start + cache_len), counted from the oldest live token:
  *         s_i = softmax_scale * (Hn q_m) . k^_i  -  b_mi,

@@ -22,7 +22,8 @@ KVQ_KEYS_PER_TOKEN, KVQ_KEYS_PER_CHANNEL = 0, 1
 # Every symbol declared in include/kvq.h.
 EXPORTED = (
     "kvq_cache_bytes", "kvq_cache_create", "kvq_cache_destroy", "kvq_cache_len", "kvq_cache_reset",
-    "kvq_cache_truncate", "kvq_cache_evict", "kvq_cache_set_rotation_signs", "kvq_quantize_append", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
+    "kvq_cache_truncate", "kvq_cache_evict", "kvq_cache_set_rotation_signs", "kvq_quantize_append",
+    "kvq_quantize_append_static", "kvq_chunk_attention", "kvq_chunk_attention_fp32",
     "kvq_chunk_attention_ex", "kvq_attention_diagnostics",
     "kvq_cache_export", "kvq_status_string", "kvq_version",
 )
@@ -70,6 +71,7 @@ def lib() -> ctypes.CDLL:
     L.kvq_cache_evict.argtypes = [vp, i64]
     L.kvq_cache_set_rotation_signs.argtypes = [vp, ctypes.c_char_p]
     L.kvq_quantize_append.argtypes = [vp, vp, vp, i64, i64, i64, vp]
+    L.kvq_quantize_append_static.argtypes = [vp, vp, vp, i64, i64, i64, vp]
     att = [vp, i64, i64, vp, vp, vp, i64, i64, i64, i64, cf, ci, vp, vp, vp]
     L.kvq_chunk_attention.argtypes = att
     L.kvq_chunk_attention_fp32.argtypes = att
@@ -205,6 +207,19 @@ def kvq_quantize_append(cache: Cache, k: torch.Tensor, v: torch.Tensor,
         raise ValueError("k and v must share strides")
     _check(lib().kvq_quantize_append(cache.handle, k.data_ptr(), v.data_ptr(), k.shape[0], st, sh, _stream(stream)),
            "kvq_quantize_append")
+
+
+def kvq_quantize_append_static(cache: Cache, k: torch.Tensor, v: torch.Tensor,
+                               stream: Optional[torch.cuda.Stream] = None) -> None:
+    """kvq_quantize_append with the per-channel work space in the library's static device array."""
+    if k.dtype != cache.torch_dtype or v.dtype != cache.torch_dtype or k.shape != v.shape:
+        raise ValueError("k and v must share the cache's io dtype and one shape")
+    _check_shape(k, cache.desc.num_heads, cache.desc.head_dim, "k and v")
+    st, sh = _tok_head_strides(k)
+    if _tok_head_strides(v) != (st, sh):
+        raise ValueError("k and v must share strides")
+    _check(lib().kvq_quantize_append_static(cache.handle, k.data_ptr(), v.data_ptr(), k.shape[0], st, sh,
+                                            _stream(stream)), "kvq_quantize_append_static")
 
 
 def _attention(fn, cache: Cache, cache_start: int, cache_len: int, q, k_cur, v_cur, softmax_scale, correction,

@@ -208,10 +208,12 @@ kvq_status kvq_cache_truncate(kvq_cache *cache, int64_t new_len)
     return KVQ_OK;
 }
 
-kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
-                               int64_t stride_token, int64_t stride_head, void *hip_stream)
+static kvq_status quantize_append_common(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                                         int64_t stride_token, int64_t stride_head, void *hip_stream, bool static_scratch)
 {
     if (!cache || n_tokens < 0) return KVQ_ERR_INVALID_ARG;
+    if (static_scratch && (int64_t)cache->desc.num_heads * cache->desc.head_dim > kvq::kStaticScratchChannels)
+        return KVQ_ERR_CAPACITY;
     if (n_tokens == 0) return KVQ_OK;
     const kvq_cache_desc &d = cache->desc;
     if (!tensor_ok(k, stride_token, stride_head, d.head_dim, d.io_dtype) ||
@@ -232,7 +234,7 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
         cache->status_clean = true;
     }
     const hipError_t e = kvq::launch_quantize_append(cache->view, k, v, cache->base + cache->len, n_tokens, stride_token,
-                                                     stride_head, slot, static_cast<hipStream_t>(hip_stream));
+                                                     stride_head, slot, static_cast<hipStream_t>(hip_stream), static_scratch);
     if (e != hipSuccess) return KVQ_ERR_HIP;
     if (d.key_axis == KVQ_KEYS_PER_CHANNEL) {
         cache->blocks.push_back(kvq_block{slot, cache->base + cache->len, n_tokens});
@@ -240,6 +242,18 @@ kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, i
     }
     cache->len += n_tokens;
     return KVQ_OK;
+}
+
+kvq_status kvq_quantize_append(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                               int64_t stride_token, int64_t stride_head, void *hip_stream)
+{
+    return quantize_append_common(cache, k, v, n_tokens, stride_token, stride_head, hip_stream, false);
+}
+
+kvq_status kvq_quantize_append_static(kvq_cache *cache, const void *k, const void *v, int64_t n_tokens,
+                                      int64_t stride_token, int64_t stride_head, void *hip_stream)
+{
+    return quantize_append_common(cache, k, v, n_tokens, stride_token, stride_head, hip_stream, true);
 }
 
 static kvq_status attention_common(const kvq_cache *cache, int64_t cache_start, int64_t cache_len,

@@ -157,9 +157,13 @@ hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t
 
 // Launchers implemented in the kernel translation units.  All return hipError_t of the launch.
 // block_slot: slot of the block this append creates (KVQ_KEYS_PER_CHANNEL caches only).
+// static_scratch: the per-channel work space of the append (ranges, L / range, zero-points per head and channel)
+// is taken from the library's static device array instead of the cache storage.
 hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
                                   int64_t n_tokens, int64_t stride_token, int64_t stride_head, int block_slot,
-                                  hipStream_t stream);
+                                  hipStream_t stream, bool static_scratch = false);
+// Largest num_heads * head_dim that the static work space serves.
+constexpr int kStaticScratchChannels = 8192;
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream);
 // Clears the status block (first append after kvq_cache_create / kvq_cache_reset).

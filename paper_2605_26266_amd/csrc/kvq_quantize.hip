@@ -16,10 +16,42 @@
 // The kernel moves d*elt bytes in and d*bits/8 + 8 bytes out per vector and no byte twice, but it is not bound by
 // that traffic: the exact double-precision rotation and the rounding decisions are about 800 vector instructions
 // per thread, and the vector ALU is busy for most of the kernel's time (about a third of the HBM rate is reached).
+#include <mutex>
+
 #include "kvq_internal.h"
 
 namespace kvq {
 namespace {
+
+// Work space of kvq_quantize_append_static: per (head, channel) the range of the block being appended (two ordered
+// 64-bit keys), L / range and the zero-point -- 32 bytes each, for at most kStaticScratchChannels of them (256 KiB,
+// held by every GPU the library runs on until the process ends).  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device (static_scratch_pointer) and every launch
+// takes that pointer as an argument.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchChannels * 32];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (each GPU holds its own copy at its own address).
+hipError_t static_scratch_pointer(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 template <typename T> struct Vec;
 template <> struct Vec<uint16_t> {  // bf16
@@ -792,10 +824,24 @@ hipError_t launch_q(const CacheView &cv, const void *k, const void *v, int64_t o
 
 }  // namespace
 
-hipError_t launch_quantize_append(const CacheView &cv, const void *k, const void *v, int64_t old_len,
+hipError_t launch_quantize_append(const CacheView &cv_in, const void *k, const void *v, int64_t old_len,
                                   int64_t n_tokens, int64_t stride_token, int64_t stride_head, int block_slot,
-                                  hipStream_t stream)
+                                  hipStream_t stream, bool static_scratch)
 {
+    CacheView cv = cv_in;
+    if (static_scratch && cv.key_axis == KVQ_KEYS_PER_CHANNEL) {
+        // The three work arrays move to the static array; the first launch of the append fills the ranges with
+        // their empty values, so what an earlier call left there does not matter.
+        const int64_t hd = (int64_t)cv.num_heads * cv.head_dim;
+        if (hd > kStaticScratchChannels) return hipErrorInvalidValue;   // (the entry point has refused this already)
+        void *base = nullptr;
+        const hipError_t e = static_scratch_pointer(&base);
+        if (e != hipSuccess) return e;
+        unsigned char *p = static_cast<unsigned char *>(base);
+        cv.kc_range = reinterpret_cast<unsigned long long *>(p);
+        cv.kc_inv = reinterpret_cast<double *>(p + hd * 16);
+        cv.kc_z = reinterpret_cast<double *>(p + hd * 24);
+    }
     const bool bf16 = cv.io_dtype == KVQ_BF16;
 #define KVQ_Q(D, B)                                                                                                         \
     if (cv.head_dim == D && cv.bits == B)                                                                                   \

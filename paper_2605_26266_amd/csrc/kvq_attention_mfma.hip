@@ -1182,6 +1182,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             }
             pf.cop = *reinterpret_cast<const u32x4 *>(buf + St::kCop + (tl * 64 + lane) * 4);
         };
+        uint32_t stage_lo_flag = 0u;   // "some low zero-point part is nonzero" of the stage that holds the tile in hand
         // tl_: IntC<t mod 4> where the caller knows it at compile time (the unrolled fast loop), IntC<-1> otherwise.
         auto fused_iteration = [&](auto tl_, int t, Prefetched &pf, f32x16 (&sn)[kRB], float (&e)[kRB][16], float (&tmax)[kRB],
                                    u32x4 (&pop)[kRB][2], uint32_t &lo_flag) {
@@ -1207,7 +1208,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const u32x4 h1 = *reinterpret_cast<const u32x4 *>(bufc + St::kVzHi + pos / 2 + 4);
                 zh[0] = h0.x; zh[1] = h0.y; zh[2] = h0.z; zh[3] = h0.w; zh[4] = h1.x; zh[5] = h1.y; zh[6] = h1.z; zh[7] = h1.w;
             }
-            const u32x2 lo_flags = *reinterpret_cast<const u32x2 *>(bufc + St::kFlags);
+            // The flags belong to the stage: the unrolled loop reads them with the stage's first tile only.
+            if constexpr (TL <= 0) {
+                const u32x2 lo_flags = *reinterpret_cast<const u32x2 *>(bufc + St::kFlags);
+                stage_lo_flag = lo_flags.x | lo_flags.y;
+            }
             uint32_t off = lo_off;
             asm volatile("" : "+v"(off));
             const uint32_t *qlo = q_stage + off;
@@ -1315,7 +1320,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 pop[rb][0].x = pw[rb][0]; pop[rb][0].y = pw[rb][1]; pop[rb][0].z = pw[rb][2]; pop[rb][0].w = pw[rb][3];
                 pop[rb][1].x = pw[rb][4]; pop[rb][1].y = pw[rb][5]; pop[rb][1].z = pw[rb][6]; pop[rb][1].w = pw[rb][7];
             }
-            lo_flag = lo_flags.x | lo_flags.y;
+            lo_flag = stage_lo_flag;
             // key codes of the tile after next (its stage has been opened at the top of this iteration)
             if constexpr (TL < 0) prefetch_keys(t + 2, pf);
             else prefetch_keys_at(TL >= 2 ? bufx : bufc, (TL + 2) & 3, pf);
@@ -1338,8 +1343,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 for (int v = V0; v < V0 + 4 * kRB; v += 2) mx[RB] = __builtin_fmaxf(__builtin_fmaxf(mx[RB], e[RB][v]), e[RB][v + 1]);
                 KVQ_CHUNK_FENCE();
             });
+            // tmax: the maximum over this lane's 16 keys of each row block.  The loop only asks whether any lane is
+            // over the threshold; the other half of the row is brought in (max_halves) when the loop has been left.
 #pragma unroll
-            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(mx[rb]);
+            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = mx[rb];
         };
         // Zero-points whose OFFSET + z needs a second bf16 piece (magnitude above 256) are rare.  The loader
         // flags the stages that hold one; the fast loop only carries the flag and is left after such a tile,
@@ -1385,6 +1392,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 add_low_zero_points(t - 1, pop);
                 lo_flag = 0u;
             }
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) tmax[rb] = max_halves(tmax[rb]);   // (a fused iteration leaves per-lane maxima)
             move_reference(e, tmax);
             // fast loop: nothing in here touches the accumulators except the MFMAs
             if constexpr (KVQ_UNROLL_STAGE && kVs) {

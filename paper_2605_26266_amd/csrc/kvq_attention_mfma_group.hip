@@ -1,7 +1,6 @@
 // Matrix-core chunk attention for caches with several (scale, zero-point) groups per token:
 // BF16 I/O, head_dim 128, FP8-E4M3 scales and BF16 zero-points per group of 32 or 64 rotated channels
-// (the storage format of the paper's "Effective bitwidth" formula, B + 24/g); 2-bit codes with either
-// group size, 4-bit codes with groups of 64.
+// (the storage format of the paper's "Effective bitwidth" formula, B + 24/g); 2- or 4-bit codes.
 //
 // The structure is that of the per-token kernel (kvq_attention_mfma.hip: transposed products, one wave
 // per 64 query rows, lazy reference maximum, hand-interleaved pipeline); what changes is where the
@@ -110,11 +109,20 @@ template <int BITS, int G> struct GStage {
     static constexpr int kWords = kTau + kStageTiles * 2 * 2 * 8 * 4;
 };
 
+// Low query parts.  Those of the first kLoResident 16-channel slabs stay in accumulation registers, the others in
+// LDS, rows kLoRowWords apart.  4-bit codes with groups of 32 have the largest stage buffers (three of 33 KB); with
+// all eight slabs in LDS (70 KB) the workgroup would need more than the 160 KB a compute unit has, with six (53 KB)
+// it fits.  In that variant the high parts are staged through the (still unused) stage buffers in the prologue.
+template <int BITS, int G> struct LoLayout {
+    static constexpr int kResident = (BITS == 4 && G == 4) ? 2 : 0;
+    static constexpr int kRowWords = kResident ? (8 - kResident) * 8 + 4 : kQRowWords;
+};
+
 template <int BITS, int G> constexpr size_t group_lds_bytes()
 {
     // stage buffers (the prologue's row constants live in them before the first stage is committed) |
     // low parts of q~ (also staging for the query prep and the V^T tiles)
-    return sizeof(uint32_t) * (kGBuffers * GStage<BITS, G>::kWords + kRowsPerBlock * kQRowWords);
+    return sizeof(uint32_t) * (kGBuffers * GStage<BITS, G>::kWords + kRowsPerBlock * LoLayout<BITS, G>::kRowWords);
 }
 
 template <int BITS, bool CORR, int G>
@@ -131,6 +139,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
     extern __shared__ __align__(16) uint32_t lds[];
     uint32_t *q_stage = lds + kGBuffers * St::kWords;
     float *row_scal = reinterpret_cast<float *>(lds);   // [row][G][4]: S_j, W_j, -nu'_j; prologue only
+    constexpr int kLoRes = LoLayout<BITS, G>::kResident, kLoRowWords = LoLayout<BITS, G>::kRowWords;
+    // staging of the high parts (and of the resident low parts) in the prologue: rows kQRowWords apart
+    uint32_t *hi_stage = kLoRes ? lds + kRowsPerBlock * G * 4 : q_stage;
+    static_assert(!kLoRes || kRowsPerBlock * G * 4 + kRowsPerBlock * kQRowWords <= kGBuffers * St::kWords, "staging fits the stage buffers");
+    static_assert(kRowsPerBlock * kLoRowWords >= 2 * D * 20 + 2 * kTileTokens * kQRowWords, "the current-chunk phase stages V^T and K tiles here");
 
     const CacheView &cv = a.cv;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -208,7 +221,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
         const float cq = c_log * 0.088388347648318f;
 #pragma unroll
         for (int i = 0; i < D; ++i) x[i] *= cq * (float)(1 << (2 * key_channel_class<BITS>(i)));
-        uint32_t *dst = q_stage + prow * kQRowWords;
+        uint32_t *dst = hi_stage + prow * kQRowWords;
+        uint32_t *dst_lo = q_stage + prow * kLoRowWords;
 #pragma unroll
         for (int i = 0; i < D / 8; ++i) {
             u32x4 w;
@@ -217,7 +231,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
         }
         __syncthreads();
-        const uint32_t *hsrc = q_stage + (wave * kRowsPerWave + n) * kQRowWords + 4 * hh;
+        const uint32_t *hsrc = hi_stage + (wave * kRowsPerWave + n) * kQRowWords + 4 * hh;
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
@@ -243,7 +257,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             }
             u32x4 w;
             w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
-            *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+            // eight channels = half a slab: the resident slabs go back through the staging rows, the others to their place
+            if (i < 2 * kLoRes) *reinterpret_cast<u32x4 *>(dst + 4 * i) = w;
+            else *reinterpret_cast<u32x4 *>(dst_lo + 4 * (i - 2 * kLoRes)) = w;
         }
 #pragma unroll
         for (int j = 0; j < G; ++j) {
@@ -282,8 +298,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             rowop[c][rb].z = hh ? w[1][2] : w[0][2]; rowop[c][rb].w = hh ? w[1][3] : w[0][3];
         }
     }
-    __syncthreads();   // the row constants are dead: the loader may now write the stage buffers
-    const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kQRowWords + 4 * hh);  // words into q_stage
+    u32x4 lo_res[kRB][kLoRes > 0 ? kLoRes : 1];
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb)
+#pragma unroll
+        for (int s = 0; s < kLoRes; ++s) {
+            lo_res[rb][s] = *reinterpret_cast<const u32x4 *>(hi_stage + (wave * kRowsPerWave + 32 * rb + n) * kQRowWords + 4 * hh + 8 * s);
+            asm volatile("" : "+a"(lo_res[rb][s]));
+        }
+    __syncthreads();   // the row constants and the staging rows are dead: the loader may now write the stage buffers
+    const uint32_t lo_off = (uint32_t)((wave * kRowsPerWave + n) * kLoRowWords + 4 * hh);  // words into q_stage
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
@@ -602,7 +626,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
                 const u32x4 kop = scaled_key_operand(s_, pf.kw, ks);
                 u32x4 lo[kRB];
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb) lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                for (int rb = 0; rb < kRB; ++rb) {
+                    if constexpr (SLAB < kLoRes) lo[rb] = lo_res[rb][SLAB];
+                    else lo[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kLoRowWords + 8 * (SLAB - kLoRes));
+                }
 #pragma unroll
                 for (int rb = 0; rb < kRB; ++rb) sn[rb] = mfma_f16(kop, qop[rb][SLAB], sn[rb]);
 #pragma unroll
@@ -699,8 +726,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
             static_for<8>([&](auto s_) {
                 constexpr int SLAB = decltype(s_)::value;
 #pragma unroll
-                for (int rb = 0; rb < kRB; ++rb)
-                    lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kQRowWords + 8 * SLAB);
+                for (int rb = 0; rb < kRB; ++rb) {
+                    if constexpr (SLAB < kLoRes) lo_nxt[rb] = lo_res[rb][SLAB];
+                    else lo_nxt[rb] = *reinterpret_cast<const u32x4 *>(qlo + 32 * rb * kLoRowWords + 8 * (SLAB - kLoRes));
+                }
                 if constexpr (SLAB == 5) load_value_words(t, vw);
                 if constexpr (SLAB == 7) load_value_steps(bufc, t & 3, 0, vs_cur);
                 const u32x4 kop = scaled_key_operand(s_, pf.kw, ks);
@@ -898,15 +927,15 @@ template <int BITS, bool CORR, int G> hipError_t launch_group(const AttentionArg
 
 bool attention_mfma_group_supported(const CacheView &cv)
 {
-    // (4-bit codes with groups of 32 need more LDS than a workgroup can have: vector kernel)
     return cv.head_dim == D && cv.io_dtype == KVQ_BF16 && cv.meta_format == KVQ_META_FP8_BF16 &&
-           ((cv.bits == 2 && (cv.group_size == 32 || cv.group_size == 64)) || (cv.bits == 4 && cv.group_size == 64));
+           (cv.bits == 2 || cv.bits == 4) && (cv.group_size == 32 || cv.group_size == 64);
 }
 
 hipError_t launch_attention_mfma_group(const AttentionArgs &a, hipStream_t stream)
 {
     if (!attention_mfma_group_supported(a.cv)) return hipErrorInvalidValue;
     if (a.cache_len > (int64_t)0x3fffffff * kTileTokens) return hipErrorInvalidValue;
+    if (a.cv.bits == 4 && a.cv.group_size == 32) return a.correction ? launch_group<4, true, 4>(a, stream) : launch_group<4, false, 4>(a, stream);
     if (a.cv.bits == 4) return a.correction ? launch_group<4, true, 2>(a, stream) : launch_group<4, false, 2>(a, stream);
     if (a.cv.group_size == 32) return a.correction ? launch_group<2, true, 4>(a, stream) : launch_group<2, false, 4>(a, stream);
     return a.correction ? launch_group<2, true, 2>(a, stream) : launch_group<2, false, 2>(a, stream);

@@ -339,9 +339,10 @@ def test_mid_group_wise_sampled_rows(P, group):
     _sampled_case(P, "mid", 2, 48, [0, 23], group=group)
 
 
-def test_mid_group_wise_int4_sampled_rows(P):
-    """INT4 with FP8/BF16 metadata per 64 channels at the mid shape on the matrix cores."""
-    _sampled_case(P, "mid", 4, 48, [0, 23], group=64)
+@pytest.mark.parametrize("group", [64, 32])
+def test_mid_group_wise_int4_sampled_rows(P, group):
+    """INT4 with FP8/BF16 metadata per 64 or 32 channels at the mid shape on the matrix cores."""
+    _sampled_case(P, "mid", 4, 48, [0, 23], group=group)
 
 
 @pytest.mark.parametrize("correction", [1, 0])

@@ -222,7 +222,11 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     if (a.only_if_flagged && !cache_flagged(a.status)) return;
     const int c = threadIdx.x;
     const int qhead = blockIdx.y;               // query head
-    const int64_t row = blockIdx.x;
+    // One row per workgroup in an ordinary launch (gridDim.x = m); the gated launch behind a matrix-core kernel
+    // has fewer workgroups, which walk the rows (its usual fate is to return above, and a small grid does that
+    // in a few microseconds where one workgroup per row took 40 at 200 000 rows).
+    for (int64_t row = blockIdx.x; row < a.m; row += gridDim.x) {
+    __syncthreads();   // the previous row's shared arrays are no longer read
     // current keys this row sees (all of them, or under the causal mask those up to its own position)
     int64_t n_vis = a.n_cur;
     if (a.causal) {
@@ -274,6 +278,7 @@ __global__ __launch_bounds__(D) void attention_simt_kernel(AttentionArgs a)
     T *op = static_cast<T *>(a.out) + row * a.q_stride_token + (int64_t)qhead * a.q_stride_head;
     Io<T>::store(op + c, acc * inv);
     if (a.mass_cached && c == 0) a.mass_cached[(int64_t)qhead * a.m + row] = sum_s * inv;
+    }
 }
 
 // Attention-level diagnostics (attention stealing; appendices on the Jensen-Shannon divergence of the
@@ -398,7 +403,7 @@ __global__ __launch_bounds__(D) void diagnostics_simt_kernel(AttentionArgs a, co
 
 hipError_t launch_attention_simt(const AttentionArgs &a, hipStream_t stream)
 {
-    const dim3 grid((unsigned)a.m, (unsigned)(a.cv.num_heads * a.q_per_kv));
+    const dim3 grid((unsigned)(a.only_if_flagged && a.m > 256 ? 256 : a.m), (unsigned)(a.cv.num_heads * a.q_per_kv));
     const bool bf16 = a.cv.io_dtype == KVQ_BF16;
 #define KVQ_A(D, B)                                                                                         \
     if (a.cv.head_dim == D && a.cv.bits == B) {                                                             \

@@ -4,10 +4,17 @@
 issue-rate microbenchmarks (paper_2605_26266_amd/kvq_microbench, a measuring tool that is not part of the library)."""
 from __future__ import annotations
 
+import glob
 import os
+import shutil
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
+
+try:                                     # `python -m paper_2605_26266_amd.build` and a plain script run both work
+    from . import mfma_hazard_check
+except ImportError:                      # pragma: no cover
+    import mfma_hazard_check
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -18,6 +25,9 @@ MICROBENCH = os.path.join(HERE, "kvq_microbench")   # stand-alone issue-rate mic
 # Packed-FP32 code generation is switched off for every device translation unit.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Sources with MFMAs written as inline assembly: the wait states around them are placed in the source, and every
+# build checks the device assembly for them (mfma_hazard_check) before the object is accepted.
+HAZARD_CHECKED = {"kvq_attention_mfma.hip"}
 SOURCES = {
     "kvq_api.hip": [],
     # the quantizer's rounding decisions follow a fixed sequence of IEEE operations: no contraction
@@ -32,6 +42,12 @@ def _compile(item):
     src, extra = item
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
     cmd = ["hipcc", *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    temps = os.path.join(OBJ, "asm_" + src.replace(".hip", ""))
+    if src in HAZARD_CHECKED:            # keep the intermediate files of this compile, among them the device assembly
+        shutil.rmtree(temps, ignore_errors=True)
+        os.makedirs(temps)
+        obj_tmp = os.path.join(temps, os.path.basename(obj))
+        cmd = ["hipcc", *COMMON, *extra, "-save-temps=obj", "-c", os.path.join(CSRC, src), "-o", obj_tmp]
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -39,6 +55,15 @@ def _compile(item):
         raise RuntimeError("hipcc failed for %s:\n%s" % (src, err))
     if err.strip():
         sys.stderr.write(err + "\n")
+    if src in HAZARD_CHECKED:
+        listings = glob.glob(os.path.join(temps, "*-hip-amdgcn-amd-amdhsa-gfx950.s"))
+        if len(listings) != 1:
+            raise RuntimeError("no device assembly found for %s in %s" % (src, temps))
+        count, problems = mfma_hazard_check.check_file(listings[0])
+        if problems or count == 0:
+            raise RuntimeError("wait-state check failed for %s (%d MFMAs):\n%s" % (src, count, "\n".join(problems[:20])))
+        os.replace(obj_tmp, obj)
+        shutil.rmtree(temps, ignore_errors=True)
     return obj
 
 

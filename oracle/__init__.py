@@ -2,8 +2,10 @@
 
 Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It never imports the HIP package.
-All arithmetic lives in ``kvq_oracle.c``; this file only marshals numpy arrays
-and chains the C calls (quantize -> dequantize -> attention) per head.
+The arithmetic lives in ``kvq_oracle.c``; this file marshals numpy arrays and
+chains the C calls (quantize -> dequantize -> attention) per head.  One step is
+done here: the sign vector of the randomised rotation is applied by multiplying
+the inputs (and the cached part of the output) by +-1 in numpy, which is exact.
 """
 from __future__ import annotations
 

@@ -32,10 +32,10 @@ MFMA_MEASURED_TFLOPS = 2446.0
 HBM_PEAK_GBS = 8000.0
 # HBM bytes of one attention launch on the Large workload (per-token INT2, fp32 metadata), from rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs of this program scaled by the same counters on a plain 1 GiB elementwise kernel
-# (--calibration-copy): 224,098 KiB x 2.000 + 52,993 KiB x 1.000.  A profile figure, not measured by this run:
+# (--calibration-copy): 223,500 KiB x 2.000 + 49,920 KiB x 1.000.  A profile figure, not measured by this run:
 # it depends on the cache layout and on the placement of workgroups, which have not changed since it was taken
 # (profiles/attention_mfma_large_int2_counters.md names the library version).
-ATTENTION_TRAFFIC_BYTES_LARGE = 513.2e6
+ATTENTION_TRAFFIC_BYTES_LARGE = 508.8e6
 # What the attention kernel computes in: BF16 inputs and outputs; cached scores as FP4 codes x four FP6 query
 # pieces on the block-scaled MFMA, current scores and P*V in bf16 MFMA, fp32 accumulation and softmax.
 ARITHMETIC = "bf16 I/O; FP4 x FP6 block-scaled MFMA (cached scores), bf16 MFMA (current scores, P*V), fp32 accumulate"

@@ -525,8 +525,6 @@ def test_seeded_sweep_of_rings_and_windows(P):
     for case in range(40):
         bits = int(rng.choice([2, 4]))
         group, fp8 = [(None, False), (128, True), (32, True), (64, True)][int(rng.integers(0, 4))]
-        if bits == 4 and group == 32:
-            group = 64
         w = wl.WORKLOADS["small"].with_bits(bits)
         heads = int(rng.integers(1, 4))
         cap = 32 * int(rng.integers(2, 21))
@@ -555,7 +553,7 @@ def test_seeded_sweep_of_rings_and_windows(P):
             cache.close()
             continue
         kc, vc = np.stack(live_k), np.stack(live_v)
-        m, ncur = int(rng.integers(1, 200)), int(rng.integers(0, 100))
+        m, ncur = int(rng.integers(1, 600)), int(rng.integers(0, 100))
         start = int(rng.integers(0, len(kc)))
         clen = int(rng.integers(1, len(kc) - start + 1))
         corr = int(rng.integers(0, 2))

@@ -23,7 +23,7 @@ LIB = os.path.join(HERE, "libkvq.so")
 MICROBENCH = os.path.join(HERE, "kvq_microbench")   # stand-alone issue-rate microbenchmarks
 
 # Packed-FP32 code generation is switched off for every device translation unit.
-COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-constant-logical-operand",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # Sources with MFMAs written as inline assembly: the wait states around them are placed in the source, and every
 # build checks the device assembly for them (mfma_hazard_check) before the object is accepted.

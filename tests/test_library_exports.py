@@ -131,3 +131,12 @@ def test_binding_rejects_tensors_that_do_not_fit_the_cache(B):
     with pytest.raises(ValueError):
         B.kvq_chunk_attention_ex(cache, 0, 0, t(16, 8, 64), t(16, 4, 128), t(16, 4, 128), t(16, 8, 64), causal=True)
     cache.close()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N above 1 exits with a message before anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""

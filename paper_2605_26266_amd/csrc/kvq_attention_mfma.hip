@@ -953,21 +953,20 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             // Scales are clamped away from zero (an all-zero row has scale 0): such a key scores 0 and its
             // value contributes 2^-64 p, as good as the exact 0.
             const int g2 = 2 * value_register_class<BITS>(slot & 15);
+            // What this loader half has: the key scale, the value scale, and one zero-point term (half 0: minus the
+            // key's stored zero-point, half 1: the value's).  Picked with selects, the same instructions in both halves.
+            float m_ks = ld_half == 0 ? pre_b : pre_a;
+            float m_vs = ld_half == 0 ? pre_c : pre_b;
+            float m_z = ld_half == 0 ? pre_a : pre_c;
             if constexpr (FP8META) {   // decode what the prefetch brought
-                const uint32_t ra = __float_as_uint(pre_a), rb = __float_as_uint(pre_b), rc = __float_as_uint(pre_c);
                 const int sb = 8 * (ld_key & 3), sh = 16 * (ld_key & 1);   // the token's byte / half-word inside its word
-                if (ld_half == 0) {
-                    pre_a = -(bf16_val((uint16_t)(ra >> sh)) + Unpack<BITS>::kStoredOffset);
-                    pre_b = e4m3_low_byte(rb >> sb);
-                    pre_c = e4m3_low_byte(rc >> sb);
-                } else {
-                    pre_a = e4m3_low_byte(ra >> sb);
-                    pre_b = e4m3_low_byte(rb >> sb);
-                    pre_c = bf16_val((uint16_t)(rc >> sh)) + Unpack<BITS>::kStoredOffset;
-                }
+                const float zs = bf16_val((uint16_t)(__float_as_uint(m_z) >> sh)) + Unpack<BITS>::kStoredOffset;
+                m_ks = e4m3_low_byte(__float_as_uint(m_ks) >> sb);
+                m_vs = e4m3_low_byte(__float_as_uint(m_vs) >> sb);
+                m_z = ld_half == 0 ? -zs : zs;
             }
-            const float vs_eff = ldexpf(fmaxf(ld_half == 0 ? pre_c : pre_b, 0x1p-64f), g2);
-            const float ks_eff = fmaxf(ld_half == 0 ? pre_b : pre_a, 0x1p-40f);
+            const float vs_eff = ldexpf(fmaxf(m_vs, 0x1p-64f), g2);
+            const float ks_eff = fmaxf(m_ks, 0x1p-40f);
             // (v_rcp_f32: one unit in the last place, far inside what lambda and the row sums need; both loader
             // halves run the same instructions on the same inputs, so their pieces belong to one value)
             const float lam = pre_valid ? __log2f(vs_eff) * __builtin_amdgcn_rcpf(ks_eff) : 0.0f;
@@ -976,7 +975,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
             u32x4 cop;
             if (ld_half == 0) {
                 // -zero in two bf16 pieces (exact for |.| < 2^16), and the window mask.
-                const float nz = pre_valid ? pre_a + Unpack<BITS>::kStoredOffset : 0.0f;
+                const float nz = pre_valid ? m_z + Unpack<BITS>::kStoredOffset : 0.0f;
                 const uint16_t z_h = bf16_bits(nz);
                 const uint16_t z_l = bf16_bits(nz - bf16_val(z_h));
                 cop.x = z_h | ((uint32_t)z_h << 16); cop.y = z_h | ((uint32_t)z_l << 16);
@@ -994,7 +993,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 // derived from what the storage holds there (it need not be initialised) enters the tile.
                 // The probability of this key meets value codes unpacked with weight 4^-g: it carries 4^g
                 // (through the value scale), and tau's multiplier is BASE + 4^-g z.
-                const float vz = pre_valid ? Unpack<BITS>::kValueBase + ldexpf(pre_c - Unpack<BITS>::kStoredOffset, -g2) : 0.0f;
+                const float vz = pre_valid ? Unpack<BITS>::kValueBase + ldexpf(m_z - Unpack<BITS>::kStoredOffset, -g2) : 0.0f;
                 reinterpret_cast<float *>(buf + St::kVScale)[slot] = pre_valid ? __builtin_amdgcn_rcpf(vs_eff) : 0.0f;
                 const uint16_t v_h = bf16_bits(vz);
                 const uint16_t v_l = bf16_bits(vz - bf16_val(v_h));
@@ -1527,13 +1526,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 
 template <int BITS, bool CORR, bool FP8META, bool PERCH = false> hipError_t launch(const AttentionArgs &a, hipStream_t stream)
 {
-    static bool configured = false;  // per instantiation; the attribute is a property of the kernel
+    static std::atomic<uint64_t> configured{0};  // per instantiation and device
     const void *fn = reinterpret_cast<const void *>(&attention_mfma_kernel<BITS, CORR, FP8META, PERCH>);
-    if (!configured) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<BITS>());
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    const hipError_t ce = configure_dynamic_lds(fn, lds_bytes<BITS>(), configured);
+    if (ce != hipSuccess) return ce;
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;

@@ -908,13 +908,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_group_kernel(Atten
 
 template <int BITS, bool CORR, int G> hipError_t launch_group(const AttentionArgs &a, hipStream_t stream)
 {
-    static bool configured = false;
+    static std::atomic<uint64_t> configured{0};  // per instantiation and device
     const void *fn = reinterpret_cast<const void *>(&attention_mfma_group_kernel<BITS, CORR, G>);
-    if (!configured) {
-        const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)group_lds_bytes<BITS, G>());
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    const hipError_t ce = configure_dynamic_lds(fn, group_lds_bytes<BITS, G>(), configured);
+    if (ce != hipSuccess) return ce;
     const int row_blocks = (int)((a.m + kRowsPerBlock - 1) / kRowsPerBlock);
     const int64_t blocks = (int64_t)row_blocks * a.cv.num_heads * a.q_per_kv;
     if (blocks > 0x7fffffff) return hipErrorInvalidValue;

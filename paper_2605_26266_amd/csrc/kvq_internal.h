@@ -26,6 +26,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <tuple>
 
 #include "../../include/kvq.h"
@@ -167,6 +168,21 @@ constexpr int kStaticScratchChannels = 8192;
 hipError_t launch_export(const CacheView &cv, int which, int64_t start, int64_t count, uint8_t *codes,
                          float *scales, float *zeros, hipStream_t stream);
 // Clears the status block (first append after kvq_cache_create / kvq_cache_reset).
+// A kernel that needs more dynamic LDS than the default limit has to be told so once per device (the attribute belongs
+// to the kernel as loaded on the current device).  `done` holds one bit per device ordinal; devices beyond 63 are
+// configured on every call.
+inline hipError_t configure_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1u)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && tracked) done.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+    return e;
+}
+
 hipError_t launch_status_clear(const CacheView &cv, hipStream_t stream);
 
 // One appended block of a KVQ_KEYS_PER_CHANNEL cache inside the attended window: its parameter slot and its

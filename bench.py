@@ -46,7 +46,7 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=8)   # the first launches of a process run 5-20 % slower (clocks ramping up)
+    ap.add_argument("--warmup", type=int, default=10)  # the first launches of a process run 5-20 % slower (clocks ramping up)
     ap.add_argument("--workload", default="large", choices=["small", "mid", "large", "stream"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",

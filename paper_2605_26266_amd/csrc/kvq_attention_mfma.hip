@@ -94,6 +94,7 @@
 namespace kvq {
 namespace {
 
+#define KVQ_INT4_KEY_SHARE 1   // 4-bit key pairs share their shifts two by two (kvq_mfma_common.h)
 #include "kvq_mfma_common.h"
 
 constexpr int kBuffers = 4;    // power of two: buffer index = stage & 3
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // Channel c of the operand carries 4^g(c) (the inverse of the weight its key codes are unpacked with).
         const float cq = c_log * 0.088388347648318f;
 #pragma unroll
-        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (kFp4 ? 1.0f : (float)(1 << (2 * key_channel_class<BITS>(i))));
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (kFp4 ? 1.0f : (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(i))));
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
         uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
@@ -328,7 +329,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
             for (int c = 0; c < kPrepCh; c += 2) {
                 const uint32_t hi = pack_f16(x[c], x[c + 1]);
-                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(c)));   // both channels share a class
+                const float wgt = 1.0f / (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(c)));   // both channels share a class
                 lo_t[c] = (x[c] - f16_lo(hi)) * wgt;
                 lo_t[c + 1] = (x[c + 1] - f16_hi(hi)) * wgt;
                 mx = fmaxf(mx, fmaxf(fabsf(lo_t[c]), fabsf(lo_t[c + 1])));
@@ -374,7 +375,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const float pair = h0 + h1;
 #endif
                 ssum_w += pair;
-                ssum += pair * (1.0f / (float)(1 << (2 * key_channel_class<BITS>(8 * i + 2 * j))));
+                ssum += pair * (1.0f / (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(8 * i + 2 * j))));
             }
             u32x4 w;
             w.x = lo[0]; w.y = lo[1]; w.z = lo[2]; w.w = lo[3];
@@ -669,7 +670,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
         // Channel c of the operand carries 4^g(c) (the inverse of the weight its key codes are unpacked with).
         const float cq = c_log * 0.088388347648318f;
 #pragma unroll
-        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (float)(1 << (2 * key_channel_class<BITS>(i)));
+        for (int i = 0; i < kPrepCh; ++i) x[i] *= cq * (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(i)));
         // The staging rows hold the high parts first (read into registers below), then the low parts,
         // which stay in LDS for the whole cached-key loop.
         uint32_t *dst = q_stage + prow * kQRowWords + ppart * (kPrepCh / 2);
@@ -698,7 +699,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
 #pragma unroll
             for (int c = 0; c < kPrepCh; c += 2) {
                 const uint32_t hi = pack_f16(x[c], x[c + 1]);
-                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(c)));   // both channels share a class
+                const float wgt = 1.0f / (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(c)));   // both channels share a class
                 lo_t[c] = (x[c] - f16_lo(hi)) * wgt;
                 lo_t[c + 1] = (x[c + 1] - f16_hi(hi)) * wgt;
                 mx = fmaxf(mx, fmaxf(fabsf(lo_t[c]), fabsf(lo_t[c + 1])));
@@ -752,7 +753,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_mfma_kernel(AttentionAr
                 const float pair = h0 + h1;
 #endif
                 ssum_w += pair;
-                const float wgt = 1.0f / (float)(1 << (2 * key_channel_class<BITS>(8 * i + 2 * j)));
+                const float wgt = 1.0f / (float)(1 << (Unpack<BITS>::kClassBits * key_channel_class<BITS>(8 * i + 2 * j)));
 #if KVQ_Q_LOW_PART
                 if constexpr (PERCH)
                     ssum += ((h0 + f16_lo(lo[j])) * ch_zero[8 * i + 2 * j] + (h1 + f16_hi(lo[j])) * ch_zero[8 * i + 2 * j + 1]) * wgt;

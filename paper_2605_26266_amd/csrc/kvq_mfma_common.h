@@ -80,12 +80,18 @@ __device__ inline float dot2_bf16(uint32_t a, uint32_t b, float c)
 // other operand of the MFMA carries the inverse weight, which is exact: for keys the query channel is
 // multiplied by 4^g, for values the probability (through the value scale) is.  This saves the shift of
 // five registers in eight.  Key values are 4 + code * 4^-g (f16), value values 8 + code * 4^-g (bf16).
-// 4-bit codes: one pair per shift, 16 + code on both sides.
+// 4-bit codes: value values are 16 + code (bf16), one pair per shift.  Key values are 16 + code * 16^-g (f16): with
+// KVQ_INT4_KEY_SHARE two adjacent pairs are cut out of one shifted word, four mantissa bits apart (class g = 1 for even
+// J, 0 for odd J), and the query channel carries 16^g; without it every pair has its own shift and g = 0 (the
+// group-wise kernel multiplies the key operand by an E4M3 step, and only 16 + code keeps that product exact in f16).
 //
 // The constants are passed through an empty asm once per kernel so that the compiler keeps them in
 // registers (masks in scalars, bases in vector registers) and selects v_and_or_b32; the instruction
 // itself is emitted by the compiler, which matters because it must know about the vector write in
 // front of the matrix instruction that reads the register.
+#ifndef KVQ_INT4_KEY_SHARE
+#define KVQ_INT4_KEY_SHARE 0
+#endif
 struct UnpackConsts {
     uint32_t kmask[3], kbase, vmask[3], vbase;
 };
@@ -98,7 +104,8 @@ template <int BITS> __device__ inline UnpackConsts make_unpack_consts()
         c.vmask[0] = 0x00300030u; c.vmask[1] = 0x000c000cu; c.vmask[2] = 0x00030003u;
         c.vbase = 0x41004100u;   // bf16 8.0
     } else {
-        c.kmask[0] = c.kmask[1] = c.kmask[2] = 0x03c003c0u;
+        c.kmask[0] = c.kmask[2] = 0x03c003c0u;
+        c.kmask[1] = KVQ_INT4_KEY_SHARE ? 0x003c003cu : 0x03c003c0u;
         c.kbase = 0x4c004c00u;   // f16 16.0
         c.vmask[0] = c.vmask[1] = c.vmask[2] = 0x00780078u;
         c.vbase = 0x41804180u;   // bf16 16.0
@@ -113,7 +120,9 @@ template <int BITS> struct Unpack {
     static constexpr float kKeyBase = BITS == 2 ? 4.0f : 16.0f;
     static constexpr float kValueBase = BITS == 2 ? 8.0f : 16.0f;
     static constexpr float kStoredOffset = BITS == 2 ? 4.0f : 16.0f;   // the cache stores zero + this
-    __host__ __device__ static constexpr int weight_class(int j) { return BITS == 2 ? 2 - j % 3 : 0; }
+    // register J of a key word; the weight of class g is 2^-(kClassBits g)
+    __host__ __device__ static constexpr int weight_class(int j) { return BITS == 2 ? 2 - j % 3 : KVQ_INT4_KEY_SHARE ? 1 - (j & 1) : 0; }
+    static constexpr int kClassBits = BITS == 2 ? 2 : 4;
 };
 
 template <int SH> __device__ inline uint32_t shift(uint32_t w)
@@ -129,6 +138,11 @@ template <int BITS, int J> __device__ inline uint32_t key_pair(uint32_t w, const
         constexpr int G = Unpack<2>::weight_class(J);          // pair lands at mantissa bits 9:8, 7:6 or 5:4
         constexpr int SH = J < 3 ? 4 : J < 6 ? -2 : -8;        // shared by the registers of one group
         static_assert(2 * J + SH == 8 - 2 * G, "key pair position");
+        return (shift<SH>(w) & c.kmask[G]) | c.kbase;
+    } else if constexpr (KVQ_INT4_KEY_SHARE) {
+        constexpr int G = Unpack<4>::weight_class(J);          // pair lands at mantissa bits 9:6 or 5:2
+        constexpr int SH = J < 2 ? 2 : -6;                      // shared by two registers
+        static_assert(4 * J + SH == 6 - 4 * G, "key pair position");
         return (shift<SH>(w) & c.kmask[G]) | c.kbase;
     } else {
         return (shift<6 - 4 * J>(w) & c.kmask[0]) | c.kbase;
@@ -182,11 +196,11 @@ template <int BITS, int BLK, int S> __device__ inline u32x4 value_operand(const 
 // Weight class of query channel c (keys) and of the key held in score register v (values).
 template <int BITS> __host__ __device__ constexpr int key_channel_class(int c)
 {
-    return Unpack<BITS>::weight_class(BITS == 2 ? 4 * ((c >> 4) & 1) + ((c >> 1) & 3) : 0);
+    return Unpack<BITS>::weight_class(BITS == 2 ? 4 * ((c >> 4) & 1) + ((c >> 1) & 3) : (c >> 1) & 3);
 }
 template <int BITS> __host__ __device__ constexpr int value_register_class(int v)
 {
-    return Unpack<BITS>::weight_class(BITS == 2 ? (v >> 1) : 0);
+    return BITS == 2 ? Unpack<BITS>::weight_class(v >> 1) : 0;
 }
 
 __device__ inline float xhalf(float v) { return __shfl_xor(v, 32); }

@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)  # the first launches of a process run 5-20 % slower (clocks ramping up)
     ap.add_argument("--workload", default="large", choices=["small", "mid", "large", "stream"])
+    ap.add_argument("--bits", type=int, default=0, choices=[0, 2, 4],
+                    help="code width of the cache; 0 = the workload's own (2; the mid workload is also defined at 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the untimed side measurements (stream, mid INT2 / INT4, large with groups of 32)")
@@ -283,6 +285,11 @@ def machine_context():
     """Clocks as rocm-smi reports them after the run (None where the tool is not there): lets a reader tell a
     slow machine from a regression."""
     import subprocess
+    # Under a profiler every child process is instrumented too (its preloaded library opens the GPU in the child
+    # before rocm-smi's own interpreter hop): no children then.
+    if any("rocprof" in os.environ.get(k, "").lower() for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES", "ROCPROFILER_REGISTER_FORCE_LOAD")) \
+            or any(k.startswith("ROCPROF") for k in os.environ):
+        return None
     try:
         r = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
         card = next(iter(json.loads(r.stdout).values()))
@@ -311,6 +318,9 @@ def main():
         print(json.dumps(run_stream(args, torch, B, wl)))
         return
     w = wl.WORKLOADS[args.workload]
+    if args.bits and args.bits != w.bits:
+        w = w.with_bits(args.bits)
+        args.no_extras = True
     n_cached = w.cached_chunks
 
     def up(x):
@@ -401,7 +411,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": ARITHMETIC if not args.group else "bf16 I/O; f16 MFMA (cached scores), bf16 / f16 MFMA (current scores, P*V), fp32 accumulate",
+        "dtype": ARITHMETIC if not args.group and w.bits == 2 else "bf16 I/O; f16 MFMA (cached scores), bf16 / f16 MFMA (current scores, P*V), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": "%s: %d heads, head_dim %d, chunk %d tokens, %d cached chunks (%d tokens) INT%d "
                                "%s asymmetric after Hadamard rotation, %s metadata, correction on"
@@ -427,7 +437,7 @@ def main():
             "frac": att_tflops / MFMA_PEAK_TFLOPS,
             "frac_of_measured_peak": att_tflops / MFMA_MEASURED_TFLOPS,
             "measured_peak": MFMA_MEASURED_TFLOPS,
-            "traffic": ATTENTION_TRAFFIC_BYTES_LARGE if w.name == "large" and args.meta == "fp32" and not args.group else None,
+            "traffic": ATTENTION_TRAFFIC_BYTES_LARGE if w.name == "large" and args.meta == "fp32" and not args.group and w.bits == 2 else None,
             "traffic_source": "rocprofv3 FETCH_SIZE / WRITE_SIZE profile (profiles/), not measured by this run",
             "attention_ms_min": float(np.min(t_att)), "attention_ms_max": float(np.max(t_att)),
         },

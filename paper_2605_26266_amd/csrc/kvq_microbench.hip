@@ -40,8 +40,9 @@ enum Op { kFma, kMul, kAndOr, kShift, kCvtPk, kDot2, kExp2, kMax3 };
 // then NV independent vector instructions of kind OP).
 // CH = -1: the MFMA takes the constant 0 as its C operand (nothing accumulated, no accumulator read).
 // The loop body starts on a 64-byte boundary plus 4 * HEAD bytes: where the instructions fall relative to
-// the 32-byte instruction-fetch blocks changes the time of a dense stream of 8-byte instructions by up to
-// 30 %, so the alignment is fixed rather than left to chance (the padding is at most 15 one-cycle no-ops
+// the 64-byte instruction lines changes the time of a dense stream of 8-byte instructions by up to
+// 30 % (line_crossing_kernel below measures what one crossing costs), so the alignment is fixed rather than left to
+// chance (the padding is at most 15 one-cycle no-ops
 // per kSteps steps).
 template <int W, int CH, int NV, Op OP, int HEAD = 0>
 __global__ __launch_bounds__(256 * W, 1) void mix_kernel(float *out, uint32_t mask, uint32_t base)
@@ -257,6 +258,44 @@ int check_fp4_fp6_layout(float *out)
     return bad;
 }
 
+// What an instruction that crosses a 64-byte line costs.  The whole loop, branch included, is one asm statement that
+// starts on a 64-byte boundary, so the placement of every instruction is known: v_fma_f32 (VOP3) is 8 bytes, s_nop 4.
+//   VAR 0: 200 FMAs, aligned                       VAR 1: the same behind one s_nop (every eighth FMA crosses a line)
+//   VAR 2: 24 lines of [7 FMAs, 2 s_nop], aligned   VAR 3: the same behind one s_nop: every FMA is misaligned by 4
+//          bytes (some cross a 32-byte boundary), none crosses a 64-byte line
+#define KVQ_F1(i) "v_fma_f32 %" #i ", %" #i ", %9, 1.0\n"
+#define KVQ_F8 KVQ_F1(0) KVQ_F1(1) KVQ_F1(2) KVQ_F1(3) KVQ_F1(4) KVQ_F1(5) KVQ_F1(6) KVQ_F1(7)
+#define KVQ_F25 KVQ_F8 KVQ_F8 KVQ_F8 KVQ_F1(0)
+#define KVQ_F200 KVQ_F25 KVQ_F25 KVQ_F25 KVQ_F25 KVQ_F25 KVQ_F25 KVQ_F25 KVQ_F25
+#define KVQ_L64 KVQ_F1(0) KVQ_F1(1) KVQ_F1(2) KVQ_F1(3) KVQ_F1(4) KVQ_F1(5) KVQ_F1(6) "s_nop 0\n s_nop 0\n"
+#define KVQ_L64X8 KVQ_L64 KVQ_L64 KVQ_L64 KVQ_L64 KVQ_L64 KVQ_L64 KVQ_L64 KVQ_L64
+#define KVQ_LOOP(BODY)                                                                                          \
+    asm volatile(".p2align 6\n 1:\n" BODY "s_sub_u32 %8, %8, 1\n s_cmp_lg_u32 %8, 0\n s_cbranch_scc1 1b\n"       \
+                 : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]), "+s"(n) \
+                 : "s"(s)                                                                                       \
+                 : "scc")
+template <int VAR> __global__ __launch_bounds__(256, 1) void line_crossing_kernel(float *out, int iters, float s)
+{
+    float x[8];
+    for (int i = 0; i < 8; ++i) x[i] = s * (float)(threadIdx.x + i);
+    int n = iters;   // > 0: the loop counts down to 0
+    if constexpr (VAR == 0) KVQ_LOOP(KVQ_F200);
+    if constexpr (VAR == 1) KVQ_LOOP("s_nop 0\n" KVQ_F200);
+    if constexpr (VAR == 2) KVQ_LOOP(KVQ_L64X8 KVQ_L64X8 KVQ_L64X8);
+    if constexpr (VAR == 3) KVQ_LOOP("s_nop 0\n" KVQ_L64X8 KVQ_L64X8 KVQ_L64X8);
+    float r = (float)n;
+    for (int i = 0; i < 8; ++i) r += x[i];
+    out[blockIdx.x * 256 + threadIdx.x] = r;
+}
+template <int VAR> double line_crossing_ns(float *out)
+{
+    const int iters = 40000;
+    line_crossing_kernel<VAR><<<kBlocks, 256>>>(out, 2000, 0.001f);
+    CHECK(hipDeviceSynchronize());
+    const float ms = time_ms([&] { line_crossing_kernel<VAR><<<kBlocks, 256>>>(out, iters, 0.001f); });
+    return ms * 1e6 / iters;   // ns per loop iteration
+}
+
 __global__ void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n)
 {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
@@ -305,6 +344,16 @@ int main()
     op_row<kDot2>(out, "v_dot2_bf16");
     op_row<kExp2>(out, "v_exp_f32");
     op_row<kMax3>(out, "v_max3_f32");
+
+    printf("\n## Instructions that cross a 64-byte line (one wave per SIMD, the loop written out in asm)\n\n");
+    {
+        const double a = line_crossing_ns<0>(out), b = line_crossing_ns<1>(out), c = line_crossing_ns<2>(out), d = line_crossing_ns<3>(out);
+        printf("| loop body | ns per iteration | |\n|---|---|---|\n");
+        printf("| 200 v_fma_f32 (8 bytes each), aligned | %.1f | %.3f ns per instruction |\n", a, a / 200);
+        printf("| the same behind one 4-byte s_nop: 25 FMAs cross a line | %.1f | %.2f ns per crossing |\n", b, (b - a) / 25);
+        printf("| 24 x [7 v_fma_f32, 2 s_nop], aligned | %.1f | %.2f ns per s_nop |\n", c, (c - 168 * a / 200) / 48);
+        printf("| the same behind one s_nop: misaligned by 4 bytes, no crossing | %.1f | |\n", d);
+    }
 
     printf("\n## LDS reads, 8 waves per compute unit, conflict-free: per wave-instruction and compute unit\n\n");
     printf("| instruction | ns | bytes per ns |\n|---|---|---|\n");

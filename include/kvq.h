@@ -193,8 +193,8 @@ kvq_status kvq_quantize_append_static(kvq_cache *cache, const void *k, const voi
  * mode that always runs the fp32 vector kernel).
  * cache_len == 0 (first chunk) and n_cur == 0 are allowed, not both; m == 0 is a no-op.
  * `out` must not alias the inputs.
- * Which kernel runs: matrix cores for BF16 caches with head_dim 128 (every format but 4-bit codes with groups of
- * 32), the fp32 vector kernel otherwise.  The matrix-core kernels carry a zero-point as two 16-bit pieces, exact
+ * Which kernel runs: matrix cores for BF16 caches with head_dim 128 (every format), the fp32 vector kernel
+ * otherwise.  The matrix-core kernels carry a zero-point as two 16-bit pieces, exact
  * below 2^16.  A cache that has stored a larger one since it was created or last reset (vectors whose offset is
  * tens of thousands of times their range) is marked by the append; for such a cache the matrix-core launch
  * returns without writing and a vector-kernel launch enqueued behind it does the work, with the same results as

@@ -87,8 +87,7 @@ typedef struct {
     int32_t group_size;      /* channels of a token sharing one (scale, zero-point): 32, 64 or head_dim */
     int32_t rotate;          /* must be 1: normalised Sylvester-Hadamard rotation before quantization */
     int32_t io_dtype;        /* kvq_dtype of q/k/v/out.  KVQ_BF16 with head_dim 128 runs on the matrix cores (every
-                                format but 4-bit codes with groups of 32); fp32 I/O, head_dim 64 and the exact
-                                correction run an fp32 vector kernel */
+                                format); fp32 I/O, head_dim 64 and the exact correction run an fp32 vector kernel */
     int32_t meta_format;     /* kvq_meta_format */
     int32_t key_axis;        /* kvq_key_axis */
     int64_t capacity_tokens; /* >= 1; storage is sized for this many tokens per head */
